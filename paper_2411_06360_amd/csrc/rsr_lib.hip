@@ -1,0 +1,599 @@
+// C ABI (include/rsr.h) and the gfx950 kernels of the RSR++ vector x binary/ternary-matrix product.
+//
+// Kernel structure (one launch per product):
+//   * A workgroup stages one activation vector in LDS (plus a zero behind it for the null row
+//     index) and owns a contiguous range of column blocks, i.e. a contiguous byte range of the
+//     index streams.  Column blocks are independent (the paper's parallelisation I, Appendix C.1).
+//   * Its wavefronts take work units (one window of 2^kw row values of one block and part, see
+//     rsr_format.h) from an LDS counter.  For a unit a wavefront
+//       1. streams the unit's diagonals with 16-byte loads and gathers v[sigma(p)] from LDS into
+//          8 accumulators per lane - the segmented sums of Eq. SS2, one accumulator per segment;
+//       2. drops the sums into its private window of u in LDS (plain stores: every slot has one
+//          writer), and reads the window back in value order;
+//       3. takes the low kw levels of the RSR++ fold (Section 4.3, Algorithm 3): "sum the
+//          odd-indexed entries, then add neighbours" - three levels inside a lane's 8 consecutive
+//          values, the next six across the 64 lanes - and leaves kw sums plus the window total
+//          in a per-unit record.
+//   * The wavefront that completes the last unit of a block adds the records up: low bits sum
+//     over windows, the k-kw high levels of the fold see only window totals; the two parts of a
+//     ternary matrix are reduced separately and subtracted once (Proposition 2.1); k outputs are
+//     stored.
+// All float additions happen in a fixed order (no floating-point atomics), so results are
+// reproducible from run to run.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+
+#include "../../include/rsr.h"
+#include "rsr_format.h"
+#include "rsr_pack.h"
+
+namespace {
+
+thread_local std::string g_error;
+
+int fail(int code, const std::string& msg) {
+  g_error = msg;
+  return code;
+}
+
+#define RSR_HIP_TRY(expr)                                                                   \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      (void)hipGetLastError();                                                              \
+      return fail(RSR_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_));         \
+    }                                                                                       \
+  } while (0)
+
+constexpr uint64_t kMagic = 0x5253522b2b763031ull;  // "RSR++v01"
+
+}  // namespace
+
+struct rsr_handle {
+  uint64_t magic = 0;
+  int device = 0, num_cu = 0;
+  size_t lds_max = 0;
+  // shape
+  int64_t rows = 0, cols = 0, nblocks = 0;
+  int k = 0, kw = 0, parts = 0, last_width = 0;
+  uint32_t max_units_per_block = 0;
+  int64_t stored_rows = 0, segments = 0, nunits = 0;
+  size_t entry_bytes = 0, slot_bytes = 0, unit_bytes = 0, blk_bytes = 0;
+  // device tables
+  void* d_entries = nullptr;
+  void* d_slots = nullptr;
+  void* d_units = nullptr;
+  void* d_blk_unit = nullptr;
+  // tuning (environment overrides read at preprocess time)
+  int waves = 16, wg_per_cu = 0;
+  // host copy of the device tables, fetched on the first rsr_export_block
+  std::unique_ptr<rsr::Packed> downloaded;
+};
+
+struct rsr_host_index {
+  uint64_t magic = 0;
+  rsr::Packed P;
+};
+
+namespace {
+
+constexpr uint64_t kHostMagic = 0x525352686f737431ull;  // "RSRhost1"
+
+bool valid(const rsr_host_index* x) { return x && x->magic == kHostMagic; }
+
+void fill_info(const rsr::Packed& P, rsr_info_t* info) {
+  std::memset(info, 0, sizeof(*info));
+  info->rows = P.rows; info->cols = P.cols; info->k = P.k; info->parts = P.parts;
+  info->nblocks = P.nblocks; info->last_block_width = P.last_width;
+  info->lo_bits = P.kw; info->hi_bits = P.k - P.kw;
+  info->stored_rows = P.stored_rows; info->segments = P.segments; info->work_units = (int64_t)P.units.size();
+  info->index_bytes = (int64_t)(P.entries.size() * sizeof(uint16_t));
+  info->segment_bytes = (int64_t)(P.slots.size() * sizeof(uint16_t));
+  info->schedule_bytes = (int64_t)(P.units.size() * sizeof(rsr::Unit) + P.blk_unit.size() * sizeof(uint32_t));
+  info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
+  info->device = -1; info->compute_units = 0;
+}
+
+bool valid(const rsr_handle* h) { return h && h->magic == kMagic; }
+
+// ---------------------------------------------------------------------------------------------
+// device code
+// ---------------------------------------------------------------------------------------------
+struct KParams {
+  const uint4* entries;
+  const uint4* slots;
+  const rsr::Unit* units;
+  const uint32_t* blk_unit;
+  const void* v;
+  void* out;
+  int rows, cols, k, kw, parts, nblocks, last_width, batch;
+  int g1;        // workgroups per batch lane
+  int ucap;      // unit records per round
+  int nslot;     // block completion counters per round
+  uint32_t off_win, off_rec, off_done, off_ctr;  // LDS byte offsets
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load of 8 row indices.  RSR_NT_LOADS selects non-temporal loads for the index stream.
+__device__ __forceinline__ uint4 load_entries(const uint4* p) {
+#ifdef RSR_NT_LOADS
+  const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+#else
+  const u32x4 x = *reinterpret_cast<const u32x4*>(p);
+#endif
+  return make_uint4(x.x, x.y, x.z, x.w);
+}
+
+template <typename AT>
+__device__ __forceinline__ AT wave_sum(AT x) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) x += __shfl_xor(x, m, 64);
+  return x;
+}
+
+template <typename VT> struct Acc;
+template <> struct Acc<float> { using type = float; };
+template <> struct Acc<int8_t> { using type = int32_t; };
+
+template <typename VT, typename AT>
+__device__ __forceinline__ void gather8(const VT* __restrict__ vl, const uint4& e, AT (&acc)[8]) {
+  acc[0] += (AT)vl[e.x & 0xffffu];
+  acc[1] += (AT)vl[e.x >> 16];
+  acc[2] += (AT)vl[e.y & 0xffffu];
+  acc[3] += (AT)vl[e.y >> 16];
+  acc[4] += (AT)vl[e.z & 0xffffu];
+  acc[5] += (AT)vl[e.z >> 16];
+  acc[6] += (AT)vl[e.w & 0xffffu];
+  acc[7] += (AT)vl[e.w >> 16];
+}
+
+constexpr int kChunk = 4;  // diagonals fetched ahead of their gathers
+
+template <typename VT>
+__global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
+  using AT = typename Acc<VT>::type;
+  extern __shared__ __align__(16) unsigned char lds[];
+  VT* vl = reinterpret_cast<VT*>(lds);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  // workgroup -> (batch lane b, block range g): the `batch` siblings of a block range sit 8
+  // workgroup ids apart so that round-robin dispatch puts them on the same XCD (shared L2).
+  const int per = 8 * p.batch;
+  const int grp = blockIdx.x / per, rem = blockIdx.x % per;
+  const int b = rem >> 3;
+  const int g = grp * 8 + (rem & 7);
+  if (g >= p.g1) return;
+  const int blk_begin = (int)((int64_t)g * p.nblocks / p.g1);
+  const int blk_end = (int)((int64_t)(g + 1) * p.nblocks / p.g1);
+  if (blk_begin >= blk_end) return;
+
+  // ---- stage the activation vector; vl[rows] = 0 serves the null row index ----
+  {
+    const VT* __restrict__ v = reinterpret_cast<const VT*>(p.v) + (int64_t)b * p.rows;
+    constexpr int per16 = 16 / (int)sizeof(VT);
+    const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
+    const uint4* v16 = reinterpret_cast<const uint4*>(v);
+    uint4* l16 = reinterpret_cast<uint4*>(vl);
+    for (int i = tid; i < n16; i += blockDim.x) l16[i] = v16[i];
+    for (int i = n16 * per16 + tid; i < p.rows; i += blockDim.x) vl[i] = v[i];
+    if (tid == 0) vl[p.rows] = (VT)0;
+  }
+
+  AT* win = reinterpret_cast<AT*>(lds + p.off_win) + wave * rsr::kWindowSlots;
+  AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
+  unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
+  unsigned* ctr = reinterpret_cast<unsigned*>(lds + p.off_ctr);
+  AT* outp = reinterpret_cast<AT*>(p.out) + (int64_t)b * p.cols;
+
+  for (int rb0 = blk_begin; rb0 < blk_end;) {
+    // a round: as many consecutive blocks as there are counters and unit records
+    const uint32_t u_begin = p.blk_unit[rb0];
+    int rb1 = rb0 + 1;
+    while (rb1 < blk_end && rb1 - rb0 < p.nslot && p.blk_unit[rb1 + 1] - u_begin <= (uint32_t)p.ucap) ++rb1;
+    const uint32_t u_end = p.blk_unit[rb1];
+    for (int i = tid; i < rb1 - rb0; i += blockDim.x) done[i] = 0;
+    if (tid == 0) *ctr = 0;
+    __syncthreads();
+
+    for (;;) {
+      unsigned take = 0;
+      if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const uint32_t ui = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
+      if (ui >= u_end) break;
+
+      const rsr::Unit* __restrict__ U = p.units + ui;
+      const uint32_t entry_off = U->entry_off, slot_off = U->slot_off, block = U->block;
+      const int window = U->window, npieces = U->npieces, nt = U->nt, part = U->part, nov = U->nov;
+      const int cvec = (lane < rsr::kMaxDiag) ? (int)U->cnt8[lane] : 0;
+      const int nsl = (npieces + 7) >> 3;  // lanes that own pieces
+
+      // slot ids of this lane's 8 ranks (padding ranks point at a dummy slot)
+      uint4 sl = make_uint4(rsr::kWindow * 0x10001u, rsr::kWindow * 0x10001u, rsr::kWindow * 0x10001u,
+                            rsr::kWindow * 0x10001u);
+      if (lane < nsl) sl = p.slots[slot_off + lane];
+
+      // clear the window
+      {
+        uint4* w16 = reinterpret_cast<uint4*>(win);
+        for (int i = lane; i < rsr::kWindowSlots / 4; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
+      }
+
+      // ---- step 1: segmented sums (Eq. SS2), one accumulator per piece ----
+      AT acc[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = (AT)0;
+      const uint4* __restrict__ ep = p.entries + entry_off + lane;
+      for (int t0 = 0; t0 < nt; t0 += kChunk) {
+        uint4 e[kChunk];
+        int ct[kChunk];
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+          const int t = t0 + j;
+          ct[j] = (t < nt) ? __builtin_amdgcn_readlane(cvec, t) : 0;
+          if (lane < ct[j]) e[j] = load_entries(ep);
+          ep += ct[j];
+        }
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j)
+          if (lane < ct[j]) gather8<VT, AT>(vl, e[j], acc);
+      }
+
+      // ---- segment sums into the window (u of Algorithm 2, this window's slice) ----
+      if (lane < nsl) {
+        win[sl.x & 0xffffu] = acc[0];
+        win[sl.x >> 16] = acc[1];
+        win[sl.y & 0xffffu] = acc[2];
+        win[sl.y >> 16] = acc[3];
+        win[sl.z & 0xffffu] = acc[4];
+        win[sl.z >> 16] = acc[5];
+        win[sl.w & 0xffffu] = acc[6];
+        win[sl.w >> 16] = acc[7];
+      }
+
+      // ---- step 2: the low levels of the RSR++ fold on this window ----
+      // lane l holds the values 8l .. 8l+7 of the window: three levels in registers ...
+      AT u[8];
+      {
+        const uint4 a = reinterpret_cast<const uint4*>(win)[2 * lane];
+        const uint4 c = reinterpret_cast<const uint4*>(win)[2 * lane + 1];
+        const uint32_t raw[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
+      }
+      AT r[10];  // r[beta] = sum of u[j] over values j with bit beta set, beta < 9; r[9] = total
+      const AT s01 = u[0] + u[1], s23 = u[2] + u[3], s45 = u[4] + u[5], s67 = u[6] + u[7];
+      r[0] = (u[1] + u[3]) + (u[5] + u[7]);  // odd-indexed entries
+      r[1] = s23 + s67;                      // odd-indexed pair sums
+      r[2] = s45 + s67;                      // odd-indexed sums of four
+      const AT x = (s01 + s23) + (s45 + s67);
+      // ... and six across the lanes: lane bit beta is value bit 3 + beta
+#pragma unroll
+      for (int beta = 0; beta < 6; ++beta) r[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
+      r[9] = x;
+      if (nov > 0) {  // pieces cut off long segments: add them under their parent's value
+        AT val = (AT)0;
+        unsigned par = 0;
+        if (lane < nov) {
+          val = win[rsr::kOverflowBase + lane];
+          par = reinterpret_cast<const uint16_t*>(p.slots + slot_off + nsl)[lane];
+        }
+#pragma unroll
+        for (int beta = 0; beta < 9; ++beta) r[beta] += ((par >> beta) & 1) ? val : (AT)0;
+        r[9] += val;
+      }
+#pragma unroll
+      for (int i = 0; i < 10; ++i) r[i] = wave_sum<AT>(r[i]);
+
+      // ---- record, and completion of the block ----
+      const int slot = (int)block - rb0;
+      unsigned before = 0;
+      if (lane == 0) {
+        AT* rr = rec + (size_t)(ui - u_begin) * rsr::kRecordWords;
+#pragma unroll
+        for (int i = 0; i < 10; ++i) rr[i] = r[i];
+        rr[10] = __builtin_bit_cast(AT, (uint32_t)((part << 16) | window));
+        before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+      }
+      before = (unsigned)__builtin_amdgcn_readfirstlane(before);
+      const uint32_t ub = p.blk_unit[block], ue = p.blk_unit[block + 1];
+      if (before + 1 == ue - ub) {
+        // ---- last unit of the block: remaining fold levels, ternary combine, store ----
+        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        // comb[q][bit]: this lane's share of "sum of u[j] over values j with bit `bit` set", part q.
+        // Bits below kw come from the unit records; a higher bit sees only the window totals
+        // (the remaining levels of the fold act on the windows' sums).
+        AT comb[2][rsr::kMaxK];
+#pragma unroll
+        for (int bit = 0; bit < rsr::kMaxK; ++bit) comb[0][bit] = comb[1][bit] = (AT)0;
+        for (uint32_t j = ub + lane; j < ue; j += 64) {
+          const AT* rr = rec + (size_t)(j - u_begin) * rsr::kRecordWords;
+          const uint32_t meta = __builtin_bit_cast(uint32_t, rr[10]);
+          const int q = (int)(meta >> 16);
+          const unsigned w = meta & 0xffffu;
+          const AT tot = rr[9];
+#pragma unroll
+          for (int bit = 0; bit < rsr::kMaxK; ++bit) {
+            if (bit < p.k) {
+              AT t;
+              if (bit < rsr::kMaxWindowBits && bit < p.kw) t = rr[bit < rsr::kMaxWindowBits ? bit : 0];
+              else t = ((w >> (bit - p.kw)) & 1u) ? tot : (AT)0;
+              comb[0][bit] += (q == 0) ? t : (AT)0;
+              comb[1][bit] += (q == 1) ? t : (AT)0;
+            }
+          }
+        }
+        // value bit `bit` belongs to column k-1-bit of the block (first column most significant)
+        const int width = ((int)block == p.nblocks - 1) ? p.last_width : p.k;
+        AT mine = (AT)0;
+#pragma unroll
+        for (int bit = 0; bit < rsr::kMaxK; ++bit) {
+          if (bit < p.k) {
+            AT res = wave_sum<AT>(comb[0][bit]);
+            if (p.parts == 2) res -= wave_sum<AT>(comb[1][bit]);  // Proposition 2.1: v.B(1) - v.B(2)
+            if (lane == p.k - 1 - bit) mine = res;
+          }
+        }
+        if (lane < width) outp[(int64_t)block * p.k + lane] = mine;
+      }
+    }
+    rb0 = rb1;
+    __syncthreads();
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host code
+// ---------------------------------------------------------------------------------------------
+int env_int(const char* name, int dflt) {
+  const char* s = std::getenv(name);
+  if (!s || !*s) return dflt;
+  return std::atoi(s);
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+template <typename VT>
+int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
+  if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
+  if (!v || !out) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer");
+  if (batch < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be >= 1");
+  if (batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be <= 65535");
+
+  KParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.entries = static_cast<const uint4*>(h->d_entries);
+  p.slots = static_cast<const uint4*>(h->d_slots);
+  p.units = static_cast<const rsr::Unit*>(h->d_units);
+  p.blk_unit = static_cast<const uint32_t*>(h->d_blk_unit);
+  p.v = v;
+  p.out = out;
+  p.rows = (int)h->rows; p.cols = (int)h->cols; p.k = h->k; p.kw = h->kw; p.parts = h->parts;
+  p.nblocks = (int)h->nblocks; p.last_width = h->last_width; p.batch = batch;
+
+  // LDS budget: activation vector + per-wavefront windows + unit records + counters
+  const size_t vbytes = align_up(((size_t)h->rows + 1) * sizeof(VT), 16);
+  const size_t win_bytes = (size_t)rsr::kWindowSlots * 4;
+  const size_t rec_bytes = (size_t)rsr::kRecordWords * 4;
+  int nslot = 64;
+  size_t ucap = std::max<size_t>(h->max_units_per_block, 256);
+  int waves = h->waves;
+  auto total = [&](int w) { return vbytes + (size_t)w * win_bytes + ucap * rec_bytes + (size_t)nslot * 4 + 16; };
+  if (total(1) > h->lds_max && ucap > h->max_units_per_block) ucap = h->max_units_per_block;
+  while (waves > 1 && total(waves) > h->lds_max) waves >>= 1;
+  if (total(waves) > h->lds_max)
+    return fail(RSR_ERR_UNSUPPORTED, "activation vector of " + std::to_string(h->rows) + " rows does not fit in " +
+                                         std::to_string(h->lds_max) + " bytes of LDS");
+  const size_t lds = total(waves);
+  p.ucap = (int)ucap; p.nslot = nslot;
+  p.off_win = (uint32_t)vbytes;
+  p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
+  p.off_done = (uint32_t)(p.off_rec + ucap * rec_bytes);
+  p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
+
+  // grid: about one (or two, if LDS allows) resident workgroups per compute unit in total
+  int wg_per_cu = h->wg_per_cu > 0 ? h->wg_per_cu : (int)std::min<size_t>(2, h->lds_max / lds);
+  if (wg_per_cu < 1) wg_per_cu = 1;
+  int64_t g1 = ((int64_t)h->num_cu * wg_per_cu + batch - 1) / batch;
+  g1 = (g1 + 7) / 8 * 8;
+  if (g1 > h->nblocks) g1 = h->nblocks;
+  if (g1 < 1) g1 = 1;
+  p.g1 = (int)g1;
+  const int64_t grid = (g1 + 7) / 8 * 8 * (int64_t)batch;
+  if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
+
+  auto kern = rsr_matvec_kernel<VT>;
+  RSR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream), p);
+  RSR_HIP_TRY(hipGetLastError());
+  return RSR_OK;
+}
+
+void free_tables(rsr_handle* h) {
+  if (h->d_entries) (void)hipFree(h->d_entries);
+  if (h->d_slots) (void)hipFree(h->d_slots);
+  if (h->d_units) (void)hipFree(h->d_units);
+  if (h->d_blk_unit) (void)hipFree(h->d_blk_unit);
+  h->d_entries = h->d_slots = h->d_units = h->d_blk_unit = nullptr;
+}
+
+int upload(rsr_handle* h, const rsr::Packed& P) {
+  h->entry_bytes = P.entries.size() * sizeof(uint16_t);
+  h->slot_bytes = P.slots.size() * sizeof(uint16_t);
+  h->unit_bytes = P.units.size() * sizeof(rsr::Unit);
+  h->blk_bytes = P.blk_unit.size() * sizeof(uint32_t);
+  // 16 spare bytes keep every stream non-empty and 16-byte loads of a final granule in bounds
+  RSR_HIP_TRY(hipMalloc(&h->d_entries, h->entry_bytes + 16));
+  RSR_HIP_TRY(hipMalloc(&h->d_slots, h->slot_bytes + 16));
+  RSR_HIP_TRY(hipMalloc(&h->d_units, h->unit_bytes + 16));
+  RSR_HIP_TRY(hipMalloc(&h->d_blk_unit, h->blk_bytes + 16));
+  if (h->entry_bytes) RSR_HIP_TRY(hipMemcpy(h->d_entries, P.entries.data(), h->entry_bytes, hipMemcpyHostToDevice));
+  if (h->slot_bytes) RSR_HIP_TRY(hipMemcpy(h->d_slots, P.slots.data(), h->slot_bytes, hipMemcpyHostToDevice));
+  if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(h->d_units, P.units.data(), h->unit_bytes, hipMemcpyHostToDevice));
+  RSR_HIP_TRY(hipMemcpy(h->d_blk_unit, P.blk_unit.data(), h->blk_bytes, hipMemcpyHostToDevice));
+  RSR_HIP_TRY(hipDeviceSynchronize());
+  return RSR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
+  g_error.clear();
+  std::unique_ptr<rsr_handle> h(new (std::nothrow) rsr_handle());
+  if (!h) { fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory"); return nullptr; }
+  rsr::Packed P;
+  std::string err;
+  int rc;
+  try {
+    rc = rsr::pack_matrix(A, rows, cols, k, env_int("RSR_PACK_THREADS", 0), &P, &err);
+  } catch (const std::bad_alloc&) {
+    fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
+    return nullptr;
+  }
+  if (rc != 0) { fail(rc, "rsr_preprocess: " + err); return nullptr; }
+
+  hipError_t e = hipGetDevice(&h->device);
+  if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e)); return nullptr; }
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, h->device);
+  if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipGetDeviceProperties: ") + hipGetErrorString(e)); return nullptr; }
+  h->num_cu = prop.multiProcessorCount;
+  h->lds_max = prop.sharedMemPerBlock;
+  h->rows = P.rows; h->cols = P.cols; h->nblocks = P.nblocks;
+  h->k = P.k; h->kw = P.kw; h->parts = P.parts; h->last_width = P.last_width;
+  h->max_units_per_block = P.max_units_per_block;
+  h->stored_rows = P.stored_rows; h->segments = P.segments; h->nunits = (int64_t)P.units.size();
+  h->waves = env_int("RSR_WAVES", 16);
+  if (h->waves < 1) h->waves = 1;
+  if (h->waves > 16) h->waves = 16;
+  h->wg_per_cu = env_int("RSR_WG_PER_CU", 0);
+  if (upload(h.get(), P) != RSR_OK) { free_tables(h.get()); return nullptr; }
+  h->magic = kMagic;
+  return h.release();
+}
+
+int rsr_matvec(rsr_handle* h, const float* v, float* out, int batch, void* stream) {
+  return launch<float>(h, v, out, batch, stream);
+}
+
+int rsr_matvec_i8(rsr_handle* h, const int8_t* v, int32_t* out, int batch, void* stream) {
+  return launch<int8_t>(h, v, out, batch, stream);
+}
+
+void rsr_destroy(rsr_handle* h) {
+  if (!valid(h)) return;
+  free_tables(h);
+  h->magic = 0;
+  delete h;
+}
+
+const char* rsr_last_error(void) { return g_error.c_str(); }
+
+int rsr_info(const rsr_handle* h, rsr_info_t* info) {
+  if (!valid(h) || !info) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle or null info");
+  std::memset(info, 0, sizeof(*info));
+  info->rows = h->rows; info->cols = h->cols; info->k = h->k; info->parts = h->parts;
+  info->nblocks = h->nblocks; info->last_block_width = h->last_width;
+  info->lo_bits = h->kw; info->hi_bits = h->k - h->kw;
+  info->stored_rows = h->stored_rows; info->segments = h->segments; info->work_units = h->nunits;
+  info->index_bytes = (int64_t)h->entry_bytes;
+  info->segment_bytes = (int64_t)h->slot_bytes;
+  info->schedule_bytes = (int64_t)(h->unit_bytes + h->blk_bytes);
+  info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
+  info->device = h->device; info->compute_units = h->num_cu;
+  return RSR_OK;
+}
+
+int rsr_export_block(rsr_handle* h, int part, int64_t block, int32_t* sigma, int32_t* L) {
+  if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
+  if (!h->downloaded) {
+    std::unique_ptr<rsr::Packed> P(new (std::nothrow) rsr::Packed());
+    if (!P) return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
+    try {
+      P->entries.resize(h->entry_bytes / sizeof(uint16_t));
+      P->slots.resize(h->slot_bytes / sizeof(uint16_t));
+      P->units.resize(h->unit_bytes / sizeof(rsr::Unit));
+      P->blk_unit.resize(h->blk_bytes / sizeof(uint32_t));
+    } catch (const std::bad_alloc&) {
+      return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
+    }
+    P->rows = h->rows; P->cols = h->cols; P->k = h->k; P->kw = h->kw; P->parts = h->parts;
+    P->nblocks = h->nblocks; P->last_width = h->last_width;
+    int dev = 0;
+    RSR_HIP_TRY(hipGetDevice(&dev));
+    RSR_HIP_TRY(hipSetDevice(h->device));
+    if (h->entry_bytes) RSR_HIP_TRY(hipMemcpy(P->entries.data(), h->d_entries, h->entry_bytes, hipMemcpyDeviceToHost));
+    if (h->slot_bytes) RSR_HIP_TRY(hipMemcpy(P->slots.data(), h->d_slots, h->slot_bytes, hipMemcpyDeviceToHost));
+    if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(P->units.data(), h->d_units, h->unit_bytes, hipMemcpyDeviceToHost));
+    RSR_HIP_TRY(hipMemcpy(P->blk_unit.data(), h->d_blk_unit, h->blk_bytes, hipMemcpyDeviceToHost));
+    RSR_HIP_TRY(hipSetDevice(dev));
+    h->downloaded = std::move(P);
+  }
+  std::string err;
+  const int rc = rsr::decode_block(*h->downloaded, part, block, sigma, L, &err);
+  if (rc != 0) return fail(rc, "rsr_export_block: " + err);
+  return RSR_OK;
+}
+
+rsr_host_index* rsr_host_pack(const int8_t* A, int64_t rows, int64_t cols, int k) {
+  g_error.clear();
+  std::unique_ptr<rsr_host_index> x(new (std::nothrow) rsr_host_index());
+  if (!x) { fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory"); return nullptr; }
+  std::string err;
+  int rc;
+  try {
+    rc = rsr::pack_matrix(A, rows, cols, k, env_int("RSR_PACK_THREADS", 0), &x->P, &err);
+  } catch (const std::bad_alloc&) {
+    fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
+    return nullptr;
+  }
+  if (rc != 0) { fail(rc, "rsr_host_pack: " + err); return nullptr; }
+  x->magic = kHostMagic;
+  return x.release();
+}
+
+void rsr_host_free(rsr_host_index* x) {
+  if (!valid(x)) return;
+  x->magic = 0;
+  delete x;
+}
+
+int rsr_host_info(const rsr_host_index* x, rsr_info_t* info) {
+  if (!valid(x) || !info) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index or null info");
+  fill_info(x->P, info);
+  return RSR_OK;
+}
+
+int rsr_host_export_block(const rsr_host_index* x, int part, int64_t block, int32_t* sigma, int32_t* L) {
+  if (!valid(x)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index");
+  std::string err;
+  const int rc = rsr::decode_block(x->P, part, block, sigma, L, &err);
+  if (rc != 0) return fail(rc, "rsr_host_export_block: " + err);
+  return RSR_OK;
+}
+
+int rsr_host_streams(const rsr_host_index* x, const uint16_t** entries, int64_t* n_entries, const uint16_t** slots,
+                     int64_t* n_slots, const void** units, int64_t* n_units, const uint32_t** blk_unit) {
+  if (!valid(x)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index");
+  if (entries) *entries = x->P.entries.data();
+  if (n_entries) *n_entries = (int64_t)x->P.entries.size();
+  if (slots) *slots = x->P.slots.data();
+  if (n_slots) *n_slots = (int64_t)x->P.slots.size();
+  if (units) *units = x->P.units.data();
+  if (n_units) *n_units = (int64_t)x->P.units.size();
+  if (blk_unit) *blk_unit = x->P.blk_unit.data();
+  return RSR_OK;
+}
+
+}  // extern "C"

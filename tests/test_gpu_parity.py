@@ -1,0 +1,231 @@
+"""GPU parity: the HIP library, called through the C ABI, against the CPU oracle.
+
+int8 activations: bit-exact.  float activations: |gpu - oracle| <= 1e-5 * sum_i |v_i| per output,
+oracle accumulating in float64.  Inputs are seeded and synthetic (workloads/), at the shapes of
+the benchmark configurations; the bigger ones are checked in full because the C oracle finishes
+them in seconds.
+"""
+import numpy as np
+import pytest
+
+import paper_2411_06360_amd as R
+import workloads
+from oracle import dense, steps
+from tests.gpu_util import DeviceIndex, assert_f32_close
+
+pytestmark = pytest.mark.gpu
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def note(msg):
+    print(msg, flush=True)
+
+
+# ---- configuration 1: binary 1024^2, k = 8, int8, bit-exact -----------------------------------------
+def test_config1_binary_1k_int8_bit_exact():
+    w = workloads.get("binary_1k")
+    A, v = w.matrix(), w.activations(1, "i8")
+    note(f"config1 {A.shape} k={w.k}")
+    with DeviceIndex(A, w.k) as d:
+        got = d.matvec(v)
+        assert np.array_equal(got.astype(np.int64), dense.matvec_i8(A, v))
+        # the float path on the same matrix
+        vf = w.activations(1, "f32")
+        assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+
+
+# ---- configuration 2: ternary 4096^2, k = 10, float --------------------------------------------------
+def test_config2_ternary_4k_f32():
+    w = workloads.get("ternary_4k")
+    A, v = w.matrix(), w.activations(1, "f32")
+    note(f"config2 {A.shape} k={w.k}")
+    with DeviceIndex(A, w.k) as d:
+        assert d.info.parts == 2 and d.info.nblocks == 410 and d.info.last_block_width == 6
+        worst = assert_f32_close(d.matvec(v), dense.matvec_f32(A, v), v)
+        note(f"  worst error / bound = {worst:.3g}")
+        v8 = w.activations(2, "i8")
+        assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+
+
+# ---- small shapes: several tiles, ragged tails, every k ------------------------------------------------
+SMALL = [
+    # rows, cols, k, kind
+    (1, 1, 1, "binary"), (6, 6, 2, "binary"), (50, 37, 3, "ternary"), (300, 64, 8, "binary"),
+    (257, 100, 10, "ternary"), (1024, 48, 12, "binary"), (700, 26, 13, "ternary"), (100, 33, 16, "ternary"),
+    (2000, 20, 5, "binary"), (4097, 130, 9, "ternary"), (513, 1000, 7, "ternary"), (3, 5000, 4, "ternary"),
+]
+
+
+@pytest.mark.parametrize("rows,cols,k,kind", SMALL)
+def test_small_shapes_int8_exact_and_f32_close(rows, cols, k, kind):
+    g = rng(rows * 7 + cols * 3 + k)
+    A = (g.integers(0, 2, size=(rows, cols)) if kind == "binary" else g.integers(-1, 2, size=(rows, cols))).astype(np.int8)
+    note(f"small {rows}x{cols} k={k} {kind}")
+    with DeviceIndex(A, k) as d:
+        for batch in (1, 3):
+            v8 = g.integers(-127, 128, size=(batch, rows), dtype=np.int8)
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+            vf = g.standard_normal((batch, rows)).astype(np.float32)
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+
+
+def test_k_invariance_same_matrix_every_k():
+    g = rng(41)
+    A = g.integers(-1, 2, size=(600, 70)).astype(np.int8)
+    v8 = g.integers(-127, 128, size=600, dtype=np.int8)
+    vf = g.standard_normal(600).astype(np.float32)
+    want8, wantf = dense.matvec_i8(A, v8), dense.matvec_f32(A, vf)
+    for k in range(1, 17):
+        note(f"k-invariance k={k}")
+        with DeviceIndex(A, k) as d:
+            assert np.array_equal(d.matvec(v8).astype(np.int64), want8), k
+            assert_f32_close(d.matvec(vf), wantf, vf)
+
+
+@pytest.mark.parametrize("name", ["ones", "zeros", "identity", "equal_rows", "bin_k", "paper"])
+def test_degenerate_and_closed_form_matrices(name, golden):
+    g = rng(43)
+    rows, cols, k = 3000, 24, 6
+    if name == "ones":
+        A = np.ones((rows, cols), np.int8)
+    elif name == "zeros":
+        A = np.zeros((rows, cols), np.int8)
+    elif name == "identity":
+        rows = cols = 200
+        A = np.eye(rows, dtype=np.int8)
+    elif name == "equal_rows":
+        A = np.tile(g.integers(-1, 2, size=(1, cols)).astype(np.int8), (rows, 1))
+    elif name == "bin_k":
+        k, rows, cols = 10, 1024, 10
+        A = steps.bin_matrix(k).astype(np.int8)  # u = v: the product is the fold of v
+    else:
+        A = np.array(golden["matrix_B"]["rows"], dtype=np.int8)
+        k = 2
+    rows = A.shape[0]
+    note(f"degenerate {name} {A.shape} k={k}")
+    v8 = g.integers(-127, 128, size=rows, dtype=np.int8)
+    vf = g.standard_normal(rows).astype(np.float32)
+    with DeviceIndex(A, k) as d:
+        got8 = d.matvec(v8).astype(np.int64)
+        assert np.array_equal(got8, dense.matvec_i8(A, v8))
+        gotf = d.matvec(vf)
+        assert_f32_close(gotf, dense.matvec_f32(A, vf), vf)
+        if name == "ones":
+            assert np.all(got8 == int(v8.astype(np.int64).sum()))
+        if name == "zeros":
+            assert np.all(got8 == 0) and np.all(gotf == 0)
+        if name == "identity":
+            assert np.array_equal(got8, v8.astype(np.int64)) and np.array_equal(gotf, vf)
+        if name == "paper":
+            d8 = np.array(golden["derived_product"]["v"], dtype=np.int8)
+            assert d.matvec(d8).tolist() == golden["derived_product"]["v_dot_B"]
+
+
+def test_tables_on_the_device_are_the_papers_index(golden):
+    B = np.array(golden["matrix_B"]["rows"], dtype=np.int8)
+    with DeviceIndex(B, 2) as d:
+        sigma, L = R.rsr_export_block(d.handle, 0, 0)
+        assert (sigma + 1).tolist() == golden["example_3_3"]["sigma_1based"]
+        assert (L[:-1] + 1).tolist() == golden["example_3_3"]["full_segmentation_1based"]
+    g = rng(47)
+    A = g.integers(-1, 2, size=(900, 45)).astype(np.int8)
+    with DeviceIndex(A, 10) as d:
+        for p, Bp in enumerate(steps.ternary_split(A)):
+            for b, Bi in enumerate(steps.column_blocks(Bp, 10)):
+                sigma, L = R.rsr_export_block(d.handle, p, b)
+                assert np.array_equal(sigma, steps.binary_row_order(Bi))
+                assert np.array_equal(L[:-1], steps.full_segmentation(Bi)) and L[-1] == 900
+
+
+def test_results_are_reproducible_and_batch_equals_single_calls():
+    w = workloads.get("ternary_4k")
+    A = w.matrix()[:2048, :777].copy()
+    g = rng(53)
+    vf = g.standard_normal((5, 2048)).astype(np.float32)
+    v8 = g.integers(-127, 128, size=(5, 2048), dtype=np.int8)
+    with DeviceIndex(A, 10) as d:
+        a, b = d.matvec(vf), d.matvec(vf)
+        assert np.array_equal(a, b)  # fixed summation order
+        singles = np.stack([d.matvec(vf[i]) for i in range(5)])
+        assert np.array_equal(a, singles)
+        assert np.array_equal(d.matvec(v8), np.stack([d.matvec(v8[i]) for i in range(5)]))
+
+
+def test_unaligned_activation_pointer_and_odd_row_count():
+    import torch
+
+    g = rng(59)
+    rows, cols, k = 1001, 90, 8
+    A = g.integers(-1, 2, size=(rows, cols)).astype(np.int8)
+    with DeviceIndex(A, k) as d:
+        vf = g.standard_normal((3, rows)).astype(np.float32)  # lanes 1, 2 start at a non-16-byte offset
+        assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+        v8 = g.integers(-127, 128, size=(3, rows), dtype=np.int8)
+        assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+        # a base pointer that is itself only 4-byte aligned
+        buf = torch.zeros(rows + 1, dtype=torch.float32, device="cuda")
+        buf[1:] = torch.from_numpy(vf[0]).cuda()
+        out = torch.empty(cols, dtype=torch.float32, device="cuda")
+        R.rsr_matvec(d.handle, buf[1:], out, 1, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert_f32_close(out.cpu().numpy(), dense.matvec_f32(A, vf[0]), vf[0])
+
+
+def test_errors_from_the_device_entry_points():
+    import torch
+
+    A = np.zeros((41000, 8), np.int8)
+    A[::2] = 1
+    with DeviceIndex(A, 4) as d:  # float vector of 41000 rows (164 KB) cannot sit in LDS; int8 can
+        v = torch.zeros(41000, dtype=torch.float32, device="cuda")
+        out = torch.zeros(8, dtype=torch.float32, device="cuda")
+        with pytest.raises(R.RsrError) as e:
+            R.rsr_matvec(d.handle, v, out, 1, None)
+        assert e.value.code == -2
+        v8 = np.ones(41000, np.int8)
+        assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec(d.handle, v, out, 0, None)
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec(d.handle, None, out, 1, None)
+
+
+# ---- the big configurations, in full ----------------------------------------------------------------------
+def test_config3_binary_16k_f32_and_int8_batches():
+    w = workloads.get("binary_16k")
+    A = w.matrix()
+    note(f"config3 {A.shape} k={w.k}")
+    with DeviceIndex(A, w.k) as d:
+        assert d.info.nblocks == 1366 and d.info.last_block_width == 4 and d.info.parts == 1
+        for batch in (1, 8):
+            vf = w.activations(batch, "f32")
+            worst = assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf, threads=dense.host_threads()), vf)
+            note(f"  f32 batch {batch}: worst error / bound = {worst:.3g}")
+            v8 = w.activations(batch, "i8")
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8, threads=dense.host_threads()))
+
+
+@pytest.mark.parametrize("idx", range(7))
+def test_config4_llm_block_matrices(idx):
+    w = workloads.CONFIGS[4][idx]
+    A = w.matrix()
+    note(f"config4 {w.name} {A.shape} k={w.k}")
+    with DeviceIndex(A, w.k) as d:
+        assert d.info.parts == 2
+        for batch in (1, 16):
+            vf = w.activations(batch, "f32")
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf, threads=dense.host_threads()), vf)
+
+
+def test_config5_correlated_ternary_32k_batch4():
+    w = workloads.get("ternary_32k_correlated")
+    A = w.matrix()
+    note(f"config5 {A.shape} k={w.k}")
+    with DeviceIndex(A, w.k) as d:
+        assert d.info.nblocks == 2521 and d.info.last_block_width == 8 and d.info.parts == 2
+        vf = w.activations(4, "f32")
+        worst = assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf, threads=dense.host_threads()), vf)
+        note(f"  worst error / bound = {worst:.3g}")
