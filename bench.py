@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the RSR++ vector x matrix product on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch B] [--regime cold|warm]
+                    [--workload NAME] [--dtype f32|i8]
+
+A "step" is one pass of the whole hot path (index stream, gather, segmented sums, fold, combine,
+store) over one batch: one rsr_matvec call.  The default workload is the binary 16384 x 16384
+matrix with block width k = 12 and one float activation vector, i.e. the configuration the
+headline metric is quoted on.  Inputs are seeded and synthetic and are resident in device memory
+before the timed region starts.
+
+Regimes: "cold" rotates the calls over enough separately allocated copies of the index that the
+working set exceeds twice the 256 MB last-level cache, so every call streams its tables from
+HBM; "warm" calls one copy back to back (cache-assisted; reported for context).
+
+Prints ONE JSON line: throughput in matvecs/s, the HBM roofline of the kernel (algorithmic bytes
+per launch = stored table bytes + activations in + results out, over the average launch duration
+measured with events on the launch stream), and the CPU oracle timed on the host cores on a
+bounded sample (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
+LLC_BYTES = 256 << 20          # last-level (Infinity) cache; the cold regime rotates over > 2x this
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3000)
+    ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--batch", type=int, default=1)
+    ap.add_argument("--regime", choices=("cold", "warm"), default="cold")
+    ap.add_argument("--workload", default="binary_16k")
+    ap.add_argument("--dtype", choices=("f32", "i8"), default="f32")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle timing leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (profiling runs)")
+    ap.add_argument("--no-check", action="store_true", help="skip the parity check before timing")
+    return ap.parse_args()
+
+
+def cpu_baseline(A, v, dtype, budget_s):
+    """The oracle as it stands, on all host cores (column stripes), for about budget_s seconds."""
+    from oracle import dense
+
+    threads = dense.host_threads()
+    fn = dense.matvec_f32 if dtype == "f32" else dense.matvec_i8
+    one = v[:1]
+    t0 = time.perf_counter()
+    fn(A, one, threads=threads)
+    first = time.perf_counter() - t0
+    reps = max(1, min(200, int(budget_s / max(first, 1e-4)) - 1))
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        fn(A, one, threads=threads)
+    dt = time.perf_counter() - t0
+    t1 = time.perf_counter()
+    fn(A, one, threads=1)
+    single = time.perf_counter() - t1
+    return {
+        "value": reps / dt,
+        "unit": "matvecs/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"{reps} full products of the same {A.shape[0]}x{A.shape[1]} matrix with one vector, "
+                  f"columns striped over {threads} threads",
+        "single_thread_matvecs_per_s": 1.0 / single,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU: --gpus {args.gpus} is not supported (column blocks shard across "
+              "GPUs without communication, but this build runs on a single device)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2411_06360_amd as R
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    w = workloads.get(args.workload)
+    A = w.matrix()
+    v = w.activations(args.batch, args.dtype)
+    rows, cols = A.shape
+
+    # ---- index copies -------------------------------------------------------------------------
+    first = R.rsr_preprocess(A, w.k)
+    info = R.rsr_info(first)
+    table_bytes = int(info.table_bytes)
+    if args.regime == "cold":
+        ncopies = max(2, -(-2 * LLC_BYTES // table_bytes) + 1)
+        ncopies = min(ncopies, 64)
+    else:
+        ncopies = 1
+    handles = [first] + [R.rsr_preprocess(A, w.k) for _ in range(ncopies - 1)]
+
+    dv = torch.from_numpy(v).cuda()
+    out_dtype = torch.float32 if args.dtype == "f32" else torch.int32
+    dout = torch.zeros((args.batch, cols), dtype=out_dtype, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    call = R.rsr_matvec if args.dtype == "f32" else R.rsr_matvec_i8
+
+    # ---- parity at full size, in the launch configuration that is timed ---------------------------
+    parity = None
+    if not args.no_check:
+        from oracle import dense
+
+        call(handles[-1], dv, dout, args.batch, stream)
+        torch.cuda.synchronize()
+        got = dout.cpu().numpy()
+        if args.dtype == "f32":
+            exact = dense.matvec_f32(A, v, threads=dense.host_threads())
+            bound = 1e-5 * np.abs(v.astype(np.float64)).sum(axis=1, keepdims=True)
+            parity = float((np.abs(got.astype(np.float64) - exact) / bound).max())
+            if not parity <= 1.0:
+                print(f"parity FAILED: error is {parity:.3g} x the allowed 1e-5*sum|v|", file=sys.stderr)
+                sys.exit(1)
+        else:
+            exact = dense.matvec_i8(A, v, threads=dense.host_threads())
+            if not np.array_equal(got.astype(np.int64), exact):
+                print("parity FAILED: int8 product is not exact", file=sys.stderr)
+                sys.exit(1)
+            parity = 0.0
+
+    # ---- timed region -------------------------------------------------------------------------------
+    lib = R.load()
+    fn = lib.rsr_matvec if args.dtype == "f32" else lib.rsr_matvec_i8
+    pv, po = dv.data_ptr(), dout.data_ptr()
+
+    def run(n, offset=0):
+        for i in range(n):
+            rc = fn(handles[(offset + i) % ncopies], pv, po, args.batch, stream)
+            if rc != 0:
+                raise RuntimeError(R.rsr_last_error())
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    run(args.steps, args.warmup)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = ev0.elapsed_time(ev1)
+
+    ms_per_step = wall * 1e3 / args.steps
+    launch_us = dev_ms * 1e3 / args.steps
+    elem = 4 if args.dtype == "f32" else 1
+    alg_bytes = table_bytes + args.batch * (rows * elem + cols * 4)
+    achieved = alg_bytes / (launch_us * 1e-6) / 1e9
+
+    result = {
+        "metric": "RSR++ v.A matvecs/s at n=16384 (binary, k=12); achieved HBM GB/s vs peak"
+                  if args.workload == "binary_16k" else f"RSR++ v.A matvecs/s ({args.workload})",
+        "value": args.batch * args.steps / wall,
+        "unit": "matvecs/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": args.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {w.kind} {rows}x{cols}, k={w.k}, batch {args.batch}, {args.dtype} activations",
+            "regime": args.regime,
+            "index_copies_rotated": ncopies,
+            "working_set_bytes": ncopies * table_bytes,
+            "table_bytes": table_bytes,
+            "stored_rows": int(info.stored_rows),
+            "segments": int(info.segments),
+            "work_units": int(info.work_units),
+            "parity_worst_error_over_bound": parity,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "algorithmic_bytes_per_launch": alg_bytes,
+            "launch_us": launch_us,
+        },
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(A, v, args.dtype, args.cpu_seconds)
+    torch.cuda.synchronize()
+    for h in handles:
+        R.rsr_destroy(h)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

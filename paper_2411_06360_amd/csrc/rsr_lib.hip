@@ -412,7 +412,6 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
 
   auto kern = rsr_matvec_kernel<VT>;
-  RSR_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream), p);
   RSR_HIP_TRY(hipGetLastError());
   return RSR_OK;
@@ -478,6 +477,12 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   if (h->waves < 1) h->waves = 1;
   if (h->waves > 16) h->waves = 16;
   h->wg_per_cu = env_int("RSR_WG_PER_CU", 0);
+  // both kernels may use the whole LDS of a compute unit as dynamic shared memory
+  for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>)}) {
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_max);
+    if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e)); return nullptr; }
+  }
   if (upload(h.get(), P) != RSR_OK) { free_tables(h.get()); return nullptr; }
   h->magic = kMagic;
   return h.release();

@@ -138,24 +138,36 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
   }
 }
 
-void pack_block(const int8_t* A, int64_t rows, int64_t cols, int k, int kw, int parts, int64_t block,
-                Scratch* S, BlockOut* out) {
-  const int64_t c0 = block * k;
-  const int width = (int)std::min<int64_t>(k, cols - c0);
-  const int shift = k - width;
-  for (int p = 0; p < parts; ++p) S->val[p].resize((size_t)rows);
-  // Definition 3.2: the row's bits, first column most significant
+constexpr int kGroup = 8;  // column blocks whose row values are extracted in one pass over A
+
+// Definition 3.2 for kGroup consecutive blocks at once: the row's bits, first column most
+// significant.  One pass over the rows reads each cache line of A once for the whole group.
+void extract_values(const int8_t* A, int64_t rows, int64_t cols, int k, int parts, int64_t block0, int nb,
+                    std::vector<uint16_t> (*val)[2]) {
+  int width[kGroup], shift[kGroup];
+  for (int g = 0; g < nb; ++g) {
+    width[g] = (int)std::min<int64_t>(k, cols - (block0 + g) * k);
+    shift[g] = k - width[g];
+    for (int p = 0; p < parts; ++p) val[g][p].resize((size_t)rows);
+  }
+  const int64_t c0 = block0 * k;
   for (int64_t r = 0; r < rows; ++r) {
     const int8_t* a = A + r * cols + c0;
-    uint32_t plus = 0, minus = 0;
-    for (int c = 0; c < width; ++c) {
-      const int x = a[c];
-      plus = (plus << 1) | (uint32_t)(x == 1);
-      minus = (minus << 1) | (uint32_t)(x == -1);
+    for (int g = 0; g < nb; ++g) {
+      uint32_t plus = 0, minus = 0;
+      for (int c = 0; c < width[g]; ++c) {
+        const int x = a[c];
+        plus = (plus << 1) | (uint32_t)(x == 1);
+        minus = (minus << 1) | (uint32_t)(x == -1);
+      }
+      a += width[g];
+      val[g][0][(size_t)r] = (uint16_t)(plus << shift[g]);
+      if (parts == 2) val[g][1][(size_t)r] = (uint16_t)(minus << shift[g]);
     }
-    S->val[0][(size_t)r] = (uint16_t)(plus << shift);
-    if (parts == 2) S->val[1][(size_t)r] = (uint16_t)(minus << shift);
   }
+}
+
+void pack_block(int64_t rows, int k, int kw, int parts, int64_t block, Scratch* S, BlockOut* out) {
   for (int p = 0; p < parts; ++p) pack_part(rows, k, kw, (uint32_t)block, p, S, out);
   if (out->units.empty()) {  // an all-zero block still has to write its outputs
     const std::vector<Piece> none;
@@ -178,7 +190,7 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
     if (threads < 1) threads = 1;
     if (threads > 16) threads = 16;
   }
-  if ((int64_t)threads > nblocks) threads = (int)nblocks;
+  if ((int64_t)threads > (nblocks + kGroup - 1) / kGroup) threads = (int)((nblocks + kGroup - 1) / kGroup);
 
   // entries must be in {-1,0,1}; any -1 makes the matrix ternary (Proposition 2.1)
   std::atomic<int64_t> bad(-1);
@@ -221,10 +233,17 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
       pool.emplace_back([&]() {
         try {
           Scratch S;
+          std::vector<uint16_t> val[kGroup][2];
           for (;;) {
-            const int64_t b = next.fetch_add(1);
-            if (b >= nblocks || failed.load()) break;
-            pack_block(A, rows, cols, k, kw, parts, b, &S, &blocks[(size_t)b]);
+            const int64_t b0 = next.fetch_add(kGroup);
+            if (b0 >= nblocks || failed.load()) break;
+            const int nb = (int)std::min<int64_t>(kGroup, nblocks - b0);
+            extract_values(A, rows, cols, k, parts, b0, nb, val);
+            for (int g = 0; g < nb; ++g) {
+              for (int p = 0; p < parts; ++p) S.val[p].swap(val[g][p]);
+              pack_block(rows, k, kw, parts, b0 + g, &S, &blocks[(size_t)(b0 + g)]);
+              for (int p = 0; p < parts; ++p) S.val[p].swap(val[g][p]);
+            }
           }
         } catch (...) {
           failed.store(1);
