@@ -46,7 +46,7 @@ class RsrInfo(ctypes.Structure):
 UNIT_DTYPE = np.dtype(
     [
         ("entry_off", "<u4"), ("slot_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("npieces", "<u2"),
-        ("nt", "u1"), ("part", "u1"), ("nov", "u1"), ("reserved0", "u1"), ("reserved1", "<u4"),
+        ("nt", "u1"), ("part", "u1"), ("nov", "u1"), ("nt_main", "u1"), ("units_in_block", "<u2"), ("main_granules", "<u2"),
         ("cnt8", "u1", (40,)),
     ]
 )

@@ -16,9 +16,15 @@
 //   * Inside a window every group of equal rows ("segment") is a piece.  Pieces are ranked by
 //     descending length; lane l of the wavefront owns ranks 8l .. 8l+7 and keeps one
 //     accumulator per rank.  Diagonal t of the window lists, for ranks 0 .. cnt_t-1 (the pieces
-//     longer than t), the t-th row of each piece, padded to a multiple of 8 with the null row
-//     index `rows` (which reads a zero kept behind the activation vector in LDS).  A lane reads
-//     its 8 entries of a diagonal with one 16-byte load; a wavefront reads one contiguous KB.
+//     longer than t), the t-th row of each piece.  Diagonals come in two tiers:
+//       - wide diagonals (t < nt_main): padded to a multiple of 8 with the null row index `rows`
+//         (which reads a zero kept behind the activation vector in LDS).  A lane reads its 8
+//         entries with one 16-byte load; a wavefront reads one contiguous KB.
+//       - tail diagonals (t >= nt_main, the first diagonal with at most 64 pieces left): stored
+//         back to back without padding; lane l reads the single entry of rank l and adds it to a
+//         ninth accumulator, which is merged into the rank's slot afterwards.  This keeps the few
+//         long segments from costing a full 8-gather step each.  The tail region as a whole is
+//         padded to 16 bytes.
 //   * A segment longer than kMaxDiag rows is cut into several pieces; the first keeps the
 //     segment's slot in the window, the others get overflow slots whose parent value is listed
 //     behind the unit's slot ids.  A window with more pieces than one unit can hold continues
@@ -48,6 +54,7 @@ constexpr int kOverflowBase = kWindow + kDummySlots;
 constexpr int kWindowSlots = kOverflowBase + kMaxOverflow;  // 584 accumulators per wavefront
 constexpr int kMaxDiag = 40;           // diagonals (rows per piece) per unit
 constexpr int kMaxK = 16;
+constexpr int kTailRanks = 64;         // a tail diagonal has at most one entry per lane
 constexpr int kMaxRows = 65534;        // 65535 values of uint16 minus the null index
 constexpr int kRecordWords = 16;       // per-unit result record in LDS: 9 low-bit sums, total, meta
 
@@ -60,9 +67,10 @@ struct alignas(16) Unit {
   uint8_t nt;          // diagonals, <= kMaxDiag
   uint8_t part;        // 0: B(1) (or binary B), 1: B(2)
   uint8_t nov;         // overflow slots in use, <= kMaxOverflow
-  uint8_t reserved0;
-  uint32_t reserved1;
-  uint8_t cnt8[kMaxDiag];  // active lanes (16-byte granules) of each diagonal, non-increasing
+  uint8_t nt_main;     // wide diagonals; diagonals nt_main .. nt-1 form the tail
+  uint16_t units_in_block;  // units of this unit's column block (all parts and windows)
+  uint16_t main_granules;   // 16-byte granules of the wide diagonals = offset of the tail region
+  uint8_t cnt8[kMaxDiag];   // wide diagonal: active lanes (16-byte granules); tail diagonal: entries
 };
 static_assert(sizeof(Unit) == 64, "unit descriptor must be 64 bytes");
 

@@ -106,13 +106,7 @@ bool valid(const rsr_handle* h) { return h && h->magic == kMagic; }
 // ---------------------------------------------------------------------------------------------
 // device code
 // ---------------------------------------------------------------------------------------------
-struct KParams {
-  const uint4* entries;
-  const uint4* slots;
-  const rsr::Unit* units;
-  const uint32_t* blk_unit;
-  const void* v;
-  void* out;
+struct KArgs {
   int rows, cols, k, kw, parts, nblocks, last_width, batch;
   int g1;        // workgroups per batch lane
   int ucap;      // unit records per round
@@ -132,11 +126,30 @@ __device__ __forceinline__ uint4 load_entries(const uint4* p) {
   return make_uint4(x.x, x.y, x.z, x.w);
 }
 
+// ---- wavefront sums with DPP (no LDS traffic).  The total ends up in lane 63. ----
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, BANK_MASK, false));
+}
+template <int CTRL, int ROW_MASK, int BANK_MASK>
+__device__ __forceinline__ int dpp_get(int x) {
+  return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, BANK_MASK, false);
+}
+// Lanes whose DPP source does not exist, or that the masks exclude, receive 0.
 template <typename AT>
-__device__ __forceinline__ AT wave_sum(AT x) {
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) x += __shfl_xor(x, m, 64);
-  return x;
+__device__ __forceinline__ AT wave_sum_to_lane63(AT x) {
+  AT y = x + dpp_get<0x111, 0xf, 0xf>(x);   // row_shr:1
+  y += dpp_get<0x112, 0xf, 0xf>(x);         // row_shr:2
+  y += dpp_get<0x113, 0xf, 0xf>(x);         // row_shr:3   -> y[i] = x[i-3..i]
+  y += dpp_get<0x114, 0xf, 0xe>(y);         // row_shr:4, lanes 4..15 of each row
+  y += dpp_get<0x118, 0xf, 0xc>(y);         // row_shr:8, lanes 8..15 -> lane 15 holds the row's sum
+  y += dpp_get<0x142, 0xa, 0xf>(y);         // row_bcast:15 into rows 1 and 3
+  y += dpp_get<0x143, 0xc, 0xf>(y);         // row_bcast:31 into rows 2 and 3 -> lane 63 holds all
+  return y;
+}
+template <typename AT>
+__device__ __forceinline__ AT lane63(AT x) {
+  return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
 template <typename VT> struct Acc;
@@ -155,16 +168,29 @@ __device__ __forceinline__ void gather8(const VT* __restrict__ vl, const uint4& 
   acc[7] += (AT)vl[e.w >> 16];
 }
 
-constexpr int kChunk = 4;  // diagonals fetched ahead of their gathers
+constexpr int kChunk = 8;  // diagonals fetched ahead of their gathers, per tier
+
+// Descriptor word w of the unit whose 16 dwords sit in lanes 0..15 of `dw`.
+__device__ __forceinline__ uint32_t desc_word(uint32_t dw, int w) {
+  return (uint32_t)__builtin_amdgcn_readlane((int)dw, w);
+}
+// Byte t of the cnt8 array, which starts at descriptor word 6.
+__device__ __forceinline__ int desc_cnt(uint32_t dw, int t) {
+  return (int)((desc_word(dw, 6 + (t >> 2)) >> ((t & 3) * 8)) & 0xffu);
+}
 
 template <typename VT>
-__global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
+__global__ void __launch_bounds__(1024)
+rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ slots,
+                  const uint32_t* __restrict__ unit_words, const uint32_t* __restrict__ blk_unit,
+                  const VT* __restrict__ vin, typename Acc<VT>::type* __restrict__ out, const KArgs p) {
   using AT = typename Acc<VT>::type;
   extern __shared__ __align__(16) unsigned char lds[];
   VT* vl = reinterpret_cast<VT*>(lds);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int nwaves = (int)(blockDim.x >> 6);
 
   // workgroup -> (batch lane b, block range g): the `batch` siblings of a block range sit 8
   // workgroup ids apart so that round-robin dispatch puts them on the same XCD (shared L2).
@@ -179,7 +205,7 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
 
   // ---- stage the activation vector; vl[rows] = 0 serves the null row index ----
   {
-    const VT* __restrict__ v = reinterpret_cast<const VT*>(p.v) + (int64_t)b * p.rows;
+    const VT* __restrict__ v = vin + (int64_t)b * p.rows;
     constexpr int per16 = 16 / (int)sizeof(VT);
     const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
     const uint4* v16 = reinterpret_cast<const uint4*>(v);
@@ -193,34 +219,66 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
   AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
   unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
   unsigned* ctr = reinterpret_cast<unsigned*>(lds + p.off_ctr);
-  AT* outp = reinterpret_cast<AT*>(p.out) + (int64_t)b * p.cols;
+  AT* outp = out + (int64_t)b * p.cols;
+  const uint32_t null_index = (uint32_t)p.rows;
 
   for (int rb0 = blk_begin; rb0 < blk_end;) {
     // a round: as many consecutive blocks as there are counters and unit records
-    const uint32_t u_begin = p.blk_unit[rb0];
+    const uint32_t u_begin = blk_unit[rb0];
     int rb1 = rb0 + 1;
-    while (rb1 < blk_end && rb1 - rb0 < p.nslot && p.blk_unit[rb1 + 1] - u_begin <= (uint32_t)p.ucap) ++rb1;
-    const uint32_t u_end = p.blk_unit[rb1];
+    while (rb1 < blk_end && rb1 - rb0 < p.nslot && blk_unit[rb1 + 1] - u_begin <= (uint32_t)p.ucap) ++rb1;
+    const uint32_t u_end = blk_unit[rb1];
     for (int i = tid; i < rb1 - rb0; i += blockDim.x) done[i] = 0;
-    if (tid == 0) *ctr = 0;
+    if (tid == 0) *ctr = (unsigned)nwaves;  // the first unit of every wavefront is fixed: u_begin + wave
+
+    // the first descriptor is fetched before the barrier so that its latency overlaps the staging
+    uint32_t ui = u_begin + (uint32_t)wave;
+    uint32_t dw = 0;
+    if (ui < u_end) dw = unit_words[(size_t)ui * 16 + (lane & 15)];
     __syncthreads();
 
-    for (;;) {
-      unsigned take = 0;
-      if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const uint32_t ui = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
-      if (ui >= u_end) break;
-
-      const rsr::Unit* __restrict__ U = p.units + ui;
-      const uint32_t entry_off = U->entry_off, slot_off = U->slot_off, block = U->block;
-      const int window = U->window, npieces = U->npieces, nt = U->nt, part = U->part, nov = U->nov;
-      const int cvec = (lane < rsr::kMaxDiag) ? (int)U->cnt8[lane] : 0;
+    while (ui < u_end) {
+      const uint32_t entry_off = desc_word(dw, 0), slot_off = desc_word(dw, 1), block = desc_word(dw, 2);
+      const uint32_t w3 = desc_word(dw, 3), w4 = desc_word(dw, 4), w5 = desc_word(dw, 5);
+      const int window = (int)(w3 & 0xffffu), npieces = (int)(w3 >> 16);
+      const int nt = (int)(w4 & 0xffu), part = (int)((w4 >> 8) & 0xffu), nov = (int)((w4 >> 16) & 0xffu);
+      const int nt_main = (int)(w4 >> 24);
+      const uint32_t units_in_block = w5 & 0xffffu, main_granules = w5 >> 16;
       const int nsl = (npieces + 7) >> 3;  // lanes that own pieces
 
-      // slot ids of this lane's 8 ranks (padding ranks point at a dummy slot)
-      uint4 sl = make_uint4(rsr::kWindow * 0x10001u, rsr::kWindow * 0x10001u, rsr::kWindow * 0x10001u,
-                            rsr::kWindow * 0x10001u);
-      if (lane < nsl) sl = p.slots[slot_off + lane];
+      // ---- issue this unit's loads: first group of wide diagonals, first group of tail diagonals,
+      //      slot ids ----
+      const uint4* __restrict__ ep = entries + entry_off + lane;
+      uint4 e[kChunk];
+      int c[kChunk];
+#pragma unroll
+      for (int j = 0; j < kChunk; ++j) {
+        c[j] = (j < nt_main) ? desc_cnt(dw, j) : 0;
+        if (lane < c[j]) e[j] = load_entries(ep);
+        ep += c[j];
+      }
+      const uint16_t* __restrict__ tp = reinterpret_cast<const uint16_t*>(entries + entry_off + main_granules) + lane;
+      const int ntail = (nt_main < nt) ? desc_cnt(dw, nt_main) : 0;  // ranks that continue into the tail
+      uint32_t ti[kChunk];
+#pragma unroll
+      for (int j = 0; j < kChunk; ++j) {
+        const int t = nt_main + j;
+        const int ct = (t < nt) ? desc_cnt(dw, t) : 0;
+        ti[j] = null_index;
+        if (lane < ct) ti[j] = *tp;
+        tp += ct;
+      }
+      uint4 sl = make_uint4(0, 0, 0, 0);
+      if (lane < nsl) sl = slots[slot_off + lane];
+      uint32_t tslot = 0;
+      if (lane < ntail) tslot = reinterpret_cast<const uint16_t*>(slots + slot_off)[lane];
+
+      // ---- take the next unit and fetch its descriptor behind this unit's loads ----
+      unsigned take = 0;
+      if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      const uint32_t ui_next = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
+      uint32_t dw_next = 0;
+      if (ui_next < u_end) dw_next = unit_words[(size_t)ui_next * 16 + (lane & 15)];
 
       // clear the window
       {
@@ -232,20 +290,33 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
       AT acc[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = (AT)0;
-      const uint4* __restrict__ ep = p.entries + entry_off + lane;
-      for (int t0 = 0; t0 < nt; t0 += kChunk) {
-        uint4 e[kChunk];
-        int ct[kChunk];
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
-          const int t = t0 + j;
-          ct[j] = (t < nt) ? __builtin_amdgcn_readlane(cvec, t) : 0;
-          if (lane < ct[j]) e[j] = load_entries(ep);
-          ep += ct[j];
-        }
+      for (int t0 = 0;;) {
 #pragma unroll
         for (int j = 0; j < kChunk; ++j)
-          if (lane < ct[j]) gather8<VT, AT>(vl, e[j], acc);
+          if (lane < c[j]) gather8<VT, AT>(vl, e[j], acc);
+        t0 += kChunk;
+        if (t0 >= nt_main) break;
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {  // more than kChunk wide diagonals: long segments only
+          c[j] = (t0 + j < nt_main) ? desc_cnt(dw, t0 + j) : 0;
+          if (lane < c[j]) e[j] = load_entries(ep);
+          ep += c[j];
+        }
+      }
+      // tail: rank l is served by lane l; lanes past a diagonal's end read the zero behind v
+      AT tacc = (AT)0;
+      for (int t0 = nt_main;;) {
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) tacc += (AT)vl[ti[j]];
+        t0 += kChunk;
+        if (t0 >= nt) break;
+#pragma unroll
+        for (int j = 0; j < kChunk; ++j) {
+          const int ct = (t0 + j < nt) ? desc_cnt(dw, t0 + j) : 0;
+          ti[j] = null_index;
+          if (lane < ct) ti[j] = *tp;
+          tp += ct;
+        }
       }
 
       // ---- segment sums into the window (u of Algorithm 2, this window's slice) ----
@@ -259,6 +330,7 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
         win[sl.w & 0xffffu] = acc[6];
         win[sl.w >> 16] = acc[7];
       }
+      if (lane < ntail) win[tslot] += tacc;  // distinct ranks have distinct slots: no two lanes collide
 
       // ---- step 2: the low levels of the RSR++ fold on this window ----
       // lane l holds the values 8l .. 8l+7 of the window: three levels in registers ...
@@ -285,30 +357,31 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
         unsigned par = 0;
         if (lane < nov) {
           val = win[rsr::kOverflowBase + lane];
-          par = reinterpret_cast<const uint16_t*>(p.slots + slot_off + nsl)[lane];
+          par = reinterpret_cast<const uint16_t*>(slots + slot_off + nsl)[lane];
         }
 #pragma unroll
         for (int beta = 0; beta < 9; ++beta) r[beta] += ((par >> beta) & 1) ? val : (AT)0;
         r[9] += val;
       }
 #pragma unroll
-      for (int i = 0; i < 10; ++i) r[i] = wave_sum<AT>(r[i]);
+      for (int i = 0; i < 10; ++i) r[i] = wave_sum_to_lane63<AT>(r[i]);
 
-      // ---- record, and completion of the block ----
+      // ---- record, and completion of the block (lane 63 holds the sums) ----
       const int slot = (int)block - rb0;
       unsigned before = 0;
-      if (lane == 0) {
+      if (lane == 63) {
         AT* rr = rec + (size_t)(ui - u_begin) * rsr::kRecordWords;
 #pragma unroll
         for (int i = 0; i < 10; ++i) rr[i] = r[i];
         rr[10] = __builtin_bit_cast(AT, (uint32_t)((part << 16) | window));
         before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
       }
-      before = (unsigned)__builtin_amdgcn_readfirstlane(before);
-      const uint32_t ub = p.blk_unit[block], ue = p.blk_unit[block + 1];
-      if (before + 1 == ue - ub) {
+      before = lane63<unsigned>(before);
+      if (before + 1 == units_in_block) {
         // ---- last unit of the block: remaining fold levels, ternary combine, store ----
         __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        const uint32_t ub = blk_unit[block];
+        const uint32_t ue = ub + units_in_block;
         // comb[q][bit]: this lane's share of "sum of u[j] over values j with bit `bit` set", part q.
         // Bits below kw come from the unit records; a higher bit sees only the window totals
         // (the remaining levels of the fold act on the windows' sums).
@@ -338,13 +411,16 @@ __global__ void __launch_bounds__(1024) rsr_matvec_kernel(const KParams p) {
 #pragma unroll
         for (int bit = 0; bit < rsr::kMaxK; ++bit) {
           if (bit < p.k) {
-            AT res = wave_sum<AT>(comb[0][bit]);
-            if (p.parts == 2) res -= wave_sum<AT>(comb[1][bit]);  // Proposition 2.1: v.B(1) - v.B(2)
+            AT res = wave_sum_to_lane63<AT>(comb[0][bit]);
+            if (p.parts == 2) res -= wave_sum_to_lane63<AT>(comb[1][bit]);  // Proposition 2.1: v.B(1) - v.B(2)
+            res = lane63<AT>(res);
             if (lane == p.k - 1 - bit) mine = res;
           }
         }
         if (lane < width) outp[(int64_t)block * p.k + lane] = mine;
       }
+      ui = ui_next;
+      dw = dw_next;
     }
     rb0 = rb1;
     __syncthreads();
@@ -369,14 +445,8 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   if (batch < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be >= 1");
   if (batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be <= 65535");
 
-  KParams p;
+  KArgs p;
   std::memset(&p, 0, sizeof(p));
-  p.entries = static_cast<const uint4*>(h->d_entries);
-  p.slots = static_cast<const uint4*>(h->d_slots);
-  p.units = static_cast<const rsr::Unit*>(h->d_units);
-  p.blk_unit = static_cast<const uint32_t*>(h->d_blk_unit);
-  p.v = v;
-  p.out = out;
   p.rows = (int)h->rows; p.cols = (int)h->cols; p.k = h->k; p.kw = h->kw; p.parts = h->parts;
   p.nblocks = (int)h->nblocks; p.last_width = h->last_width; p.batch = batch;
 
@@ -412,7 +482,10 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
 
   auto kern = rsr_matvec_kernel<VT>;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream), p);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(h->d_entries), static_cast<const uint4*>(h->d_slots),
+                     static_cast<const uint32_t*>(h->d_units), static_cast<const uint32_t*>(h->d_blk_unit), v,
+                     static_cast<typename Acc<VT>::type*>(out), p);
   RSR_HIP_TRY(hipGetLastError());
   return RSR_OK;
 }

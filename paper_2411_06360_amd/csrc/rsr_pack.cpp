@@ -50,14 +50,26 @@ void emit_unit(const std::vector<Piece>& pcs, const std::vector<uint16_t>& slot_
   u.part = (uint8_t)part;
   u.nov = (uint8_t)parents.size();
   int cnt = np;
+  int nt_main = nt;
+  int granules = 0;
   for (int t = 0; t < nt; ++t) {
     while (cnt > 0 && pcs[cnt - 1].len <= t) --cnt;
-    const int c8 = ceil_div(cnt, kPerLane);
-    u.cnt8[t] = (uint8_t)c8;
-    for (int q = 0; q < c8 * kPerLane; ++q)
-      out->entries.push_back(q < cnt ? sigma[pcs[q].start + t] : null_index);
+    if (nt_main == nt && cnt <= kTailRanks) nt_main = t;  // from here on one entry per lane suffices
+    if (t < nt_main) {
+      const int c8 = ceil_div(cnt, kPerLane);
+      u.cnt8[t] = (uint8_t)c8;
+      granules += c8;
+      for (int q = 0; q < c8 * kPerLane; ++q)
+        out->entries.push_back(q < cnt ? sigma[pcs[q].start + t] : null_index);
+    } else {
+      u.cnt8[t] = (uint8_t)cnt;
+      for (int q = 0; q < cnt; ++q) out->entries.push_back(sigma[pcs[q].start + t]);
+    }
     out->stored_rows += cnt;
   }
+  while (out->entries.size() % kPerLane) out->entries.push_back(null_index);
+  u.nt_main = (uint8_t)nt_main;
+  u.main_granules = (uint16_t)granules;
   const int ns = ceil_div(np, kPerLane) * kPerLane;
   for (int q = 0; q < ns; ++q) out->slots.push_back(q < np ? slot_ids[q] : (uint16_t)kWindow);
   const int nov = (int)parents.size();
@@ -274,8 +286,10 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
       Unit u = B.units[i];
       u.entry_off += (uint32_t)(pe / kPerLane);
       u.slot_off += (uint32_t)(ps / kPerLane);
+      u.units_in_block = (uint16_t)B.units.size();
       P.units[pu + i] = u;
     }
+    if (B.units.size() > 0xffffu) { *err = "too many work units in one column block"; return -2; }
     P.max_units_per_block = std::max<uint32_t>(P.max_units_per_block, (uint32_t)B.units.size());
     P.stored_rows += B.stored_rows;
     P.segments += B.segments;
@@ -303,7 +317,7 @@ int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32
     const uint16_t* s = &P.slots[(size_t)u.slot_off * kPerLane];
     const int ns = ceil_div(u.npieces, kPerLane) * kPerLane;
     for (int t = 0; t < u.nt; ++t) {
-      const int n = u.cnt8[t] * kPerLane;
+      const int n = (t < u.nt_main) ? u.cnt8[t] * kPerLane : u.cnt8[t];
       for (int q = 0; q < n; ++q) {
         const uint16_t row = e[q];
         if (row == null_index) continue;

@@ -164,18 +164,25 @@ def check_streams(h, S):
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
             assert U["block"] == b and U["part"] < info.parts
+            assert U["units_in_block"] == blk[b + 1] - blk[b]
             assert U["npieces"] <= TILE and U["nt"] <= MAX_DIAG and U["nov"] <= MAX_OVF
             assert U["window"] < (1 << (k - kw))
             cnt8 = U["cnt8"].astype(int)
-            nt = int(U["nt"])
-            assert np.all(cnt8[nt:] == 0)
-            assert np.all(np.diff(cnt8[:nt]) <= 0)  # active lanes only ever shrink
+            nt, ntm = int(U["nt"]), int(U["nt_main"])
+            assert ntm <= nt and np.all(cnt8[nt:] == 0)
+            per_diag = np.where(np.arange(40) < ntm, 8 * cnt8, cnt8)[:nt]  # stored entries per diagonal
+            assert np.all(np.diff(cnt8[:ntm]) <= 0) and np.all(np.diff(cnt8[ntm:nt]) <= 0)  # only ever shrink
+            assert np.all(cnt8[ntm:nt] <= 64) and np.all(cnt8[ntm:nt] >= 1)  # a tail diagonal: one entry per lane
+            assert np.all(cnt8[:ntm] * 8 > 64)  # ... and it starts as soon as 64 lanes suffice
+            assert int(U["main_granules"]) == int(cnt8[:ntm].sum())
             nsl = -(-int(U["npieces"]) // 8)
-            if nt:
-                assert cnt8[0] == nsl and cnt8[nt - 1] >= 1
+            if ntm:
+                assert cnt8[0] == nsl
             off = int(U["entry_off"]) * 8
-            n_e = 8 * int(cnt8[:nt].sum())
-            assert off + n_e <= len(entries)
+            n_e = int(per_diag.sum())
+            n_e8 = -(-n_e // 8) * 8
+            assert off + n_e8 <= len(entries)
+            assert np.all(entries[off + n_e : off + n_e8] == rows)  # the tail region is padded with nulls
             e = entries[off : off + n_e].astype(int)
             assert np.all(e <= rows)  # row index or the null index
             real = e[e < rows]
@@ -195,16 +202,18 @@ def check_streams(h, S):
             assert so + 8 * nsl + npar <= len(slots)
             parents = slots[so + 8 * nsl : so + 8 * nsl + int(U["nov"])].astype(int)
             assert set(parents.tolist()) <= set(regular.tolist())  # a cut segment keeps its first piece in place
-            # per-diagonal padding is null, and only at the tail of a diagonal
+            # padding is null and sits only at the end of a wide diagonal; tail diagonals have none
             p = off
-            lens = np.zeros(8 * nsl, dtype=int)
+            lens = np.zeros(max(8 * nsl, 64), dtype=int)
             for t in range(nt):
-                d = entries[p : p + 8 * cnt8[t]].astype(int)
+                d = entries[p : p + per_diag[t]].astype(int)
                 valid = d < rows
                 nvalid = int(valid.sum())
                 assert np.all(valid[:nvalid]) and np.all(d[nvalid:] == rows)
+                if t >= ntm:
+                    assert nvalid == per_diag[t]
                 lens[:nvalid] += 1
-                p += 8 * cnt8[t]
+                p += per_diag[t]
             assert np.all(np.diff(lens[: int(U["npieces"])]) <= 0)  # ranks are ordered by descending length
             assert np.all(lens[: int(U["npieces"])] >= 1) or int(U["npieces"]) == 0
     assert stored == info.stored_rows
@@ -232,13 +241,23 @@ def walk(h, S, v):
             nsl8 = 8 * (-(-int(U["npieces"]) // 8))
             acc = np.zeros(TILE, dtype=np.int64)
             p = int(U["entry_off"]) * 8
-            for t in range(int(U["nt"])):
+            for t in range(int(U["nt_main"])):  # wide diagonals: 8 ranks per lane
                 n = 8 * int(U["cnt8"][t])
                 acc[:n] += vl[entries[p : p + n].astype(int)]
+                p += n
+            assert p == (int(U["entry_off"]) + int(U["main_granules"])) * 8
+            tacc = np.zeros(64, dtype=np.int64)
+            for t in range(int(U["nt_main"]), int(U["nt"])):  # tail diagonals: lane l serves rank l
+                n = int(U["cnt8"][t])
+                tacc[:n] += vl[entries[p : p + n].astype(int)]
                 p += n
             so = int(U["slot_off"]) * 8
             win = np.zeros(WIN_SLOTS, dtype=np.int64)
             win[slots[so : so + nsl8].astype(int)] = acc[:nsl8]
+            ntail = int(U["cnt8"][int(U["nt_main"])]) if int(U["nt_main"]) < int(U["nt"]) else 0
+            tslots = slots[so : so + ntail].astype(int)
+            assert len(set(tslots.tolist())) == ntail
+            win[tslots] += tacc[:ntail]
             r = win[:WINDOW] @ value_bits
             tot = win[:WINDOW].sum()
             for o in range(int(U["nov"])):
