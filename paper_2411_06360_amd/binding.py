@@ -54,7 +54,8 @@ assert UNIT_DTYPE.itemsize == 64
 
 
 def lib_path() -> str:
-    return os.path.join(HERE, _LIB_NAME)
+    """The built library; RSR_LIB names another build of the same sources (kernel experiments)."""
+    return os.environ.get("RSR_LIB") or os.path.join(HERE, _LIB_NAME)
 
 
 def load() -> ctypes.CDLL:

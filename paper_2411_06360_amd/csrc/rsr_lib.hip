@@ -111,7 +111,8 @@ struct KArgs {
   int g1;        // workgroups per batch lane
   int ucap;      // unit records per round
   int nslot;     // block completion counters per round
-  uint32_t off_win, off_rec, off_done, off_ctr;  // LDS byte offsets
+  int nunits;    // unit descriptors in the index
+  uint32_t off_win, off_rec, off_done, off_ctr, off_bu;  // LDS byte offsets
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -152,6 +153,39 @@ __device__ __forceinline__ AT lane63(AT x) {
   return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
+template <typename AT>
+__device__ __forceinline__ AT read_lane(AT x, int l) {
+  return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
+}
+
+// Sums of eight values over the 16 lanes of each DPP row, all at once: after every exchange a
+// lane keeps half of its values and hands the other half to its partner, so the three halving
+// exchanges (lane xor 1, 2, 4) cost 4 + 2 + 1 additions instead of 8 each; a last exchange
+// (lane xor 8) completes the row.  On return every lane holds the row sum of v[lane & 7].
+template <typename AT>
+__device__ __forceinline__ AT row_sums_of_eight(const AT (&v)[8], int lane) {
+  const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4;
+  AT w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const AT keep = b0 ? v[2 * i + 1] : v[2 * i];
+    const AT give = b0 ? v[2 * i] : v[2 * i + 1];
+    w[i] = keep + dpp_get<0xB1, 0xf, 0xf>(give);  // quad_perm [1,0,3,2]: lane xor 1
+  }
+  AT x2[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const AT keep = b1 ? w[2 * i + 1] : w[2 * i];
+    const AT give = b1 ? w[2 * i] : w[2 * i + 1];
+    x2[i] = keep + dpp_get<0x4E, 0xf, 0xf>(give);  // quad_perm [2,3,0,1]: lane xor 2
+  }
+  const AT keep = b2 ? x2[1] : x2[0];
+  const AT give = b2 ? x2[0] : x2[1];
+  // lane xor 4: lanes 0-3 and 8-11 of a row read 4 lanes up, lanes 4-7 and 12-15 read 4 lanes down
+  const AT y = keep + dpp_get<0x104, 0xf, 0x5>(give) + dpp_get<0x114, 0xf, 0xa>(give);
+  return y + dpp_get<0x128, 0xf, 0xf>(y);  // row_ror:8 is lane xor 8 inside a row
+}
+
 template <typename VT> struct Acc;
 template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
@@ -168,7 +202,10 @@ __device__ __forceinline__ void gather8(const VT* __restrict__ vl, const uint4& 
   acc[7] += (AT)vl[e.w >> 16];
 }
 
-constexpr int kChunk = 8;  // diagonals fetched ahead of their gathers, per tier
+// Diagonals fetched ahead of their gathers (sized so that the kernel keeps 16 wavefronts per
+// compute unit, i.e. 128 registers, without spilling).
+constexpr int kChunk = 6;   // wide diagonals: 4 registers each
+constexpr int kTChunk = 8;  // tail diagonals: 1 register each
 
 // Descriptor word w of the unit whose 16 dwords sit in lanes 0..15 of `dw`.
 __device__ __forceinline__ uint32_t desc_word(uint32_t dw, int w) {
@@ -177,6 +214,30 @@ __device__ __forceinline__ uint32_t desc_word(uint32_t dw, int w) {
 // Byte t of the cnt8 array, which starts at descriptor word 6.
 __device__ __forceinline__ int desc_cnt(uint32_t dw, int t) {
   return (int)((desc_word(dw, 6 + (t >> 2)) >> ((t & 3) * 8)) & 0xffu);
+}
+
+// The scalar fields of a unit descriptor (wavefront-uniform).
+struct Desc {
+  uint32_t entry_off, slot_off, block, main_granules;
+  int window, npieces, nt, part, nov, nt_main, units_in_block, nsl, ntail;
+};
+__device__ __forceinline__ Desc decode(uint32_t dw) {
+  Desc d;
+  d.entry_off = desc_word(dw, 0);
+  d.slot_off = desc_word(dw, 1);
+  d.block = desc_word(dw, 2);
+  const uint32_t w3 = desc_word(dw, 3), w4 = desc_word(dw, 4), w5 = desc_word(dw, 5);
+  d.window = (int)(w3 & 0xffffu);
+  d.npieces = (int)(w3 >> 16);
+  d.nt = (int)(w4 & 0xffu);
+  d.part = (int)((w4 >> 8) & 0xffu);
+  d.nov = (int)((w4 >> 16) & 0xffu);
+  d.nt_main = (int)(w4 >> 24);
+  d.units_in_block = (int)(w5 & 0xffffu);
+  d.main_granules = w5 >> 16;
+  d.nsl = (d.npieces + 7) >> 3;                                     // lanes that own pieces
+  d.ntail = (d.nt_main < d.nt) ? desc_cnt(dw, d.nt_main) : 0;       // ranks that continue into the tail
+  return d;
 }
 
 template <typename VT>
@@ -203,89 +264,102 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
   const int blk_end = (int)((int64_t)(g + 1) * p.nblocks / p.g1);
   if (blk_begin >= blk_end) return;
 
-  // ---- stage the activation vector; vl[rows] = 0 serves the null row index ----
-  {
-    const VT* __restrict__ v = vin + (int64_t)b * p.rows;
-    constexpr int per16 = 16 / (int)sizeof(VT);
-    const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
-    const uint4* v16 = reinterpret_cast<const uint4*>(v);
-    uint4* l16 = reinterpret_cast<uint4*>(vl);
-    for (int i = tid; i < n16; i += blockDim.x) l16[i] = v16[i];
-    for (int i = n16 * per16 + tid; i < p.rows; i += blockDim.x) vl[i] = v[i];
-    if (tid == 0) vl[p.rows] = (VT)0;
-  }
-
   AT* win = reinterpret_cast<AT*>(lds + p.off_win) + wave * rsr::kWindowSlots;
   AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
   unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
   unsigned* ctr = reinterpret_cast<unsigned*>(lds + p.off_ctr);
+  uint32_t* bu = reinterpret_cast<uint32_t*>(lds + p.off_bu);  // first unit of the round's blocks
   AT* outp = out + (int64_t)b * p.cols;
   const uint32_t null_index = (uint32_t)p.rows;
 
-  for (int rb0 = blk_begin; rb0 < blk_end;) {
-    // a round: as many consecutive blocks as there are counters and unit records
-    const uint32_t u_begin = blk_unit[rb0];
-    int rb1 = rb0 + 1;
-    while (rb1 < blk_end && rb1 - rb0 < p.nslot && blk_unit[rb1 + 1] - u_begin <= (uint32_t)p.ucap) ++rb1;
-    const uint32_t u_end = blk_unit[rb1];
-    for (int i = tid; i < rb1 - rb0; i += blockDim.x) done[i] = 0;
-    if (tid == 0) *ctr = (unsigned)nwaves;  // the first unit of every wavefront is fixed: u_begin + wave
+  // Loads of one unit into registers.  Wide diagonals: one 16-byte granule per active lane;
+  // tail diagonals: one entry per active lane; then the slot ids.
+  uint4 e[kChunk];
+  int c[kChunk];
+  uint32_t ti[kTChunk];
+  uint4 sl = make_uint4(0, 0, 0, 0);
+  uint32_t tslot = 0;
+  const uint4* ep = entries;
+  const uint16_t* tp = reinterpret_cast<const uint16_t*>(entries);
+  auto issue_wide = [&](const Desc& d, uint32_t dwv, int t0) {
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) {
+      c[j] = (t0 + j < d.nt_main) ? desc_cnt(dwv, t0 + j) : 0;
+      if (lane < c[j]) e[j] = load_entries(ep);
+      ep += c[j];
+    }
+  };
+  auto issue_tail = [&](const Desc& d, uint32_t dwv, int t0) {
+#pragma unroll
+    for (int j = 0; j < kTChunk; ++j) {
+      const int ct = (t0 + j < d.nt) ? desc_cnt(dwv, t0 + j) : 0;
+      ti[j] = null_index;
+      if (lane < ct) ti[j] = *tp;
+      tp += ct;
+    }
+  };
+  auto issue_slots = [&](const Desc& d) {
+    if (lane < d.nsl) sl = slots[d.slot_off + lane];
+    if (lane < d.ntail) tslot = reinterpret_cast<const uint16_t*>(slots + d.slot_off)[lane];
+  };
+  auto issue_unit = [&](const Desc& d, uint32_t dwv) {
+    ep = entries + d.entry_off + lane;
+    issue_wide(d, dwv, 0);
+    tp = reinterpret_cast<const uint16_t*>(entries + d.entry_off + d.main_granules) + lane;
+    issue_tail(d, dwv, d.nt_main);
+    issue_slots(d);
+  };
 
-    // the first descriptor is fetched before the barrier so that its latency overlaps the staging
+  bool first_round = true;
+  for (int rb0 = blk_begin; rb0 < blk_end;) {
+    // ---- round set-up.  A round covers as many consecutive blocks as there are completion
+    //      counters (nslot <= 64) and unit records (ucap). ----
+    if (tid <= p.nslot) {
+      const int blk = rb0 + tid;
+      bu[tid] = blk_unit[blk < blk_end ? blk : blk_end];
+    }
+    if (tid < p.nslot) done[tid] = 0;
+    if (tid == 0) *ctr = (unsigned)nwaves;  // the first unit of every wavefront is fixed: u_begin + wave
+    // first unit of this wavefront: descriptor and loads go out before the barrier
+    const uint32_t u_begin = blk_unit[rb0];
     uint32_t ui = u_begin + (uint32_t)wave;
     uint32_t dw = 0;
-    if (ui < u_end) dw = unit_words[(size_t)ui * 16 + (lane & 15)];
+    if (ui < (uint32_t)p.nunits) dw = unit_words[(size_t)ui * 16 + (lane & 15)];
+    if (first_round) {
+      // stage the activation vector; vl[rows] = 0 serves the null row index
+      const VT* __restrict__ v = vin + (int64_t)b * p.rows;
+      constexpr int per16 = 16 / (int)sizeof(VT);
+      const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
+      const uint4* v16 = reinterpret_cast<const uint4*>(v);
+      uint4* l16 = reinterpret_cast<uint4*>(vl);
+      for (int i = tid; i < n16; i += blockDim.x) l16[i] = v16[i];
+      for (int i = n16 * per16 + tid; i < p.rows; i += blockDim.x) vl[i] = v[i];
+      if (tid == 0) vl[p.rows] = (VT)0;
+      first_round = false;
+    }
+    Desc D = decode(dw);
+    if (ui < (uint32_t)p.nunits) issue_unit(D, dw);
     __syncthreads();
+    int nblk;
+    {
+      const bool ok = (lane < p.nslot) && (rb0 + lane < blk_end) && (bu[lane + 1] - u_begin <= (uint32_t)p.ucap);
+      const uint64_t mask = __ballot(ok);
+      nblk = (~mask == 0) ? 64 : __builtin_ctzll(~mask);
+      if (nblk < 1) nblk = 1;  // a single block always fits: ucap >= the largest block
+    }
+    const int rb1 = rb0 + nblk;
+    const uint32_t u_end = bu[nblk];
 
-    while (ui < u_end) {
-      const uint32_t entry_off = desc_word(dw, 0), slot_off = desc_word(dw, 1), block = desc_word(dw, 2);
-      const uint32_t w3 = desc_word(dw, 3), w4 = desc_word(dw, 4), w5 = desc_word(dw, 5);
-      const int window = (int)(w3 & 0xffffu), npieces = (int)(w3 >> 16);
-      const int nt = (int)(w4 & 0xffu), part = (int)((w4 >> 8) & 0xffu), nov = (int)((w4 >> 16) & 0xffu);
-      const int nt_main = (int)(w4 >> 24);
-      const uint32_t units_in_block = w5 & 0xffffu, main_granules = w5 >> 16;
-      const int nsl = (npieces + 7) >> 3;  // lanes that own pieces
-
-      // ---- issue this unit's loads: first group of wide diagonals, first group of tail diagonals,
-      //      slot ids ----
-      const uint4* __restrict__ ep = entries + entry_off + lane;
-      uint4 e[kChunk];
-      int c[kChunk];
-#pragma unroll
-      for (int j = 0; j < kChunk; ++j) {
-        c[j] = (j < nt_main) ? desc_cnt(dw, j) : 0;
-        if (lane < c[j]) e[j] = load_entries(ep);
-        ep += c[j];
-      }
-      const uint16_t* __restrict__ tp = reinterpret_cast<const uint16_t*>(entries + entry_off + main_granules) + lane;
-      const int ntail = (nt_main < nt) ? desc_cnt(dw, nt_main) : 0;  // ranks that continue into the tail
-      uint32_t ti[kChunk];
-#pragma unroll
-      for (int j = 0; j < kChunk; ++j) {
-        const int t = nt_main + j;
-        const int ct = (t < nt) ? desc_cnt(dw, t) : 0;
-        ti[j] = null_index;
-        if (lane < ct) ti[j] = *tp;
-        tp += ct;
-      }
-      uint4 sl = make_uint4(0, 0, 0, 0);
-      if (lane < nsl) sl = slots[slot_off + lane];
-      uint32_t tslot = 0;
-      if (lane < ntail) tslot = reinterpret_cast<const uint16_t*>(slots + slot_off)[lane];
-
-      // ---- take the next unit and fetch its descriptor behind this unit's loads ----
+    // next unit: taken from the workgroup's counter; its descriptor is fetched a unit ahead
+    uint32_t ui_next = u_end, dw_next = 0;
+    if (ui < u_end) {
       unsigned take = 0;
       if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      const uint32_t ui_next = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
-      uint32_t dw_next = 0;
+      ui_next = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
       if (ui_next < u_end) dw_next = unit_words[(size_t)ui_next * 16 + (lane & 15)];
+    }
 
-      // clear the window
-      {
-        uint4* w16 = reinterpret_cast<uint4*>(win);
-        for (int i = lane; i < rsr::kWindowSlots / 4; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
-      }
-
+    while (ui < u_end) {
       // ---- step 1: segmented sums (Eq. SS2), one accumulator per piece ----
       AT acc[8];
 #pragma unroll
@@ -295,32 +369,39 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
         for (int j = 0; j < kChunk; ++j)
           if (lane < c[j]) gather8<VT, AT>(vl, e[j], acc);
         t0 += kChunk;
-        if (t0 >= nt_main) break;
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j) {  // more than kChunk wide diagonals: long segments only
-          c[j] = (t0 + j < nt_main) ? desc_cnt(dw, t0 + j) : 0;
-          if (lane < c[j]) e[j] = load_entries(ep);
-          ep += c[j];
-        }
+        if (t0 >= D.nt_main) break;
+        issue_wide(D, dw, t0);  // more than kChunk wide diagonals: long segments only
+      }
+      // the wide registers are free again: the next unit's wide diagonals go out now
+      Desc Dn = D;
+      const bool have_next = ui_next < u_end;
+      if (have_next) {
+        Dn = decode(dw_next);
+        ep = entries + Dn.entry_off + lane;
+        issue_wide(Dn, dw_next, 0);
       }
       // tail: rank l is served by lane l; lanes past a diagonal's end read the zero behind v
       AT tacc = (AT)0;
-      for (int t0 = nt_main;;) {
+      if (D.nt_main < D.nt) {
+        for (int t0 = D.nt_main;;) {
 #pragma unroll
-        for (int j = 0; j < kChunk; ++j) tacc += (AT)vl[ti[j]];
-        t0 += kChunk;
-        if (t0 >= nt) break;
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j) {
-          const int ct = (t0 + j < nt) ? desc_cnt(dw, t0 + j) : 0;
-          ti[j] = null_index;
-          if (lane < ct) ti[j] = *tp;
-          tp += ct;
+          for (int j = 0; j < kTChunk; ++j) tacc += (AT)vl[ti[j]];
+          t0 += kTChunk;
+          if (t0 >= D.nt) break;
+          issue_tail(D, dw, t0);
         }
+      }
+      if (have_next) {
+        tp = reinterpret_cast<const uint16_t*>(entries + Dn.entry_off + Dn.main_granules) + lane;
+        issue_tail(Dn, dw_next, Dn.nt_main);
       }
 
       // ---- segment sums into the window (u of Algorithm 2, this window's slice) ----
-      if (lane < nsl) {
+      {
+        uint4* w16 = reinterpret_cast<uint4*>(win);
+        for (int i = lane; i < rsr::kWindowSlots / 4; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
+      }
+      if (lane < D.nsl) {
         win[sl.x & 0xffffu] = acc[0];
         win[sl.x >> 16] = acc[1];
         win[sl.y & 0xffffu] = acc[2];
@@ -330,97 +411,96 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
         win[sl.w & 0xffffu] = acc[6];
         win[sl.w >> 16] = acc[7];
       }
-      if (lane < ntail) win[tslot] += tacc;  // distinct ranks have distinct slots: no two lanes collide
+      if (lane < D.ntail) win[tslot] += tacc;  // distinct ranks have distinct slots: no two lanes collide
+      if (have_next) issue_slots(Dn);
 
       // ---- step 2: the low levels of the RSR++ fold on this window ----
       // lane l holds the values 8l .. 8l+7 of the window: three levels in registers ...
       AT u[8];
       {
         const uint4 a = reinterpret_cast<const uint4*>(win)[2 * lane];
-        const uint4 c = reinterpret_cast<const uint4*>(win)[2 * lane + 1];
-        const uint32_t raw[8] = {a.x, a.y, a.z, a.w, c.x, c.y, c.z, c.w};
+        const uint4 cc = reinterpret_cast<const uint4*>(win)[2 * lane + 1];
+        const uint32_t raw[8] = {a.x, a.y, a.z, a.w, cc.x, cc.y, cc.z, cc.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
       }
-      AT r[10];  // r[beta] = sum of u[j] over values j with bit beta set, beta < 9; r[9] = total
+      // vals[0..2]: the three levels inside the lane; vals[3..6]: lane bits 0..3 (value bits 3..6);
+      // vals[7]: the lane's total, from which the two row-index bits (value bits 7, 8) and the
+      // window total follow.
+      AT vals[8];
       const AT s01 = u[0] + u[1], s23 = u[2] + u[3], s45 = u[4] + u[5], s67 = u[6] + u[7];
-      r[0] = (u[1] + u[3]) + (u[5] + u[7]);  // odd-indexed entries
-      r[1] = s23 + s67;                      // odd-indexed pair sums
-      r[2] = s45 + s67;                      // odd-indexed sums of four
+      vals[0] = (u[1] + u[3]) + (u[5] + u[7]);  // odd-indexed entries
+      vals[1] = s23 + s67;                      // odd-indexed pair sums
+      vals[2] = s45 + s67;                      // odd-indexed sums of four
       const AT x = (s01 + s23) + (s45 + s67);
-      // ... and six across the lanes: lane bit beta is value bit 3 + beta
 #pragma unroll
-      for (int beta = 0; beta < 6; ++beta) r[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
-      r[9] = x;
-      if (nov > 0) {  // pieces cut off long segments: add them under their parent's value
+      for (int beta = 0; beta < 4; ++beta) vals[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
+      vals[7] = x;
+      AT ov7 = (AT)0, ov8 = (AT)0, ovt = (AT)0;
+      if (D.nov > 0) {  // pieces cut off long segments: add them under their parent's value
         AT val = (AT)0;
         unsigned par = 0;
-        if (lane < nov) {
+        if (lane < D.nov) {
           val = win[rsr::kOverflowBase + lane];
-          par = reinterpret_cast<const uint16_t*>(slots + slot_off + nsl)[lane];
+          par = reinterpret_cast<const uint16_t*>(slots + D.slot_off + D.nsl)[lane];
         }
 #pragma unroll
-        for (int beta = 0; beta < 9; ++beta) r[beta] += ((par >> beta) & 1) ? val : (AT)0;
-        r[9] += val;
+        for (int beta = 0; beta < 7; ++beta) vals[beta] += ((par >> beta) & 1) ? val : (AT)0;
+        ov7 = lane63<AT>(wave_sum_to_lane63<AT>(((par >> 7) & 1) ? val : (AT)0));
+        ov8 = lane63<AT>(wave_sum_to_lane63<AT>(((par >> 8) & 1) ? val : (AT)0));
+        ovt = lane63<AT>(wave_sum_to_lane63<AT>(val));
       }
-#pragma unroll
-      for (int i = 0; i < 10; ++i) r[i] = wave_sum_to_lane63<AT>(r[i]);
-
-      // ---- record, and completion of the block (lane 63 holds the sums) ----
-      const int slot = (int)block - rb0;
+      const AT rowsum = row_sums_of_eight<AT>(vals, lane);
+      win[lane] = rowsum;  // the window has been read: its first 64 slots carry the four rows across
+      // ---- record, and completion of the block: lanes 0..7 finish the sums ----
+      const int slot = (int)D.block - rb0;
       unsigned before = 0;
-      if (lane == 63) {
+      if (lane < 8) {
+        const AT r0 = win[lane], r1 = win[16 + lane], r2 = win[32 + lane], r3 = win[48 + lane];
         AT* rr = rec + (size_t)(ui - u_begin) * rsr::kRecordWords;
-#pragma unroll
-        for (int i = 0; i < 10; ++i) rr[i] = r[i];
-        rr[10] = __builtin_bit_cast(AT, (uint32_t)((part << 16) | window));
-        before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+        rr[lane == 7 ? 9 : lane] = ((r0 + r1) + (r2 + r3)) + (lane == 7 ? ovt : (AT)0);
+        if (lane == 7) {
+          rr[7] = (r1 + r3) + ov7;  // lane bit 4 = rows 1 and 3 = value bit 7
+          rr[8] = (r2 + r3) + ov8;  // lane bit 5 = rows 2 and 3 = value bit 8
+          rr[10] = __builtin_bit_cast(AT, (uint32_t)((D.part << 16) | D.window));
+          before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
       }
-      before = lane63<unsigned>(before);
-      if (before + 1 == units_in_block) {
+      before = read_lane<unsigned>(before, 7);
+      if ((int)before + 1 == D.units_in_block) {
         // ---- last unit of the block: remaining fold levels, ternary combine, store ----
+        // Lane (bit + 16 * part) adds up, over the block's units, "sum of u[j] over the values j
+        // with bit `bit` set".  Bits below kw are in the unit records; a higher bit sees only
+        // window totals (the remaining levels of the fold act on the windows' sums).
         __atomic_thread_fence(__ATOMIC_ACQUIRE);
-        const uint32_t ub = blk_unit[block];
-        const uint32_t ue = ub + units_in_block;
-        // comb[q][bit]: this lane's share of "sum of u[j] over values j with bit `bit` set", part q.
-        // Bits below kw come from the unit records; a higher bit sees only the window totals
-        // (the remaining levels of the fold act on the windows' sums).
-        AT comb[2][rsr::kMaxK];
-#pragma unroll
-        for (int bit = 0; bit < rsr::kMaxK; ++bit) comb[0][bit] = comb[1][bit] = (AT)0;
-        for (uint32_t j = ub + lane; j < ue; j += 64) {
-          const AT* rr = rec + (size_t)(j - u_begin) * rsr::kRecordWords;
+        const int bit = lane & 15, q = lane >> 4;
+        const AT* rr = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
+        const int word = (bit < p.kw) ? bit : 9;
+        AT sum = (AT)0;
+        for (int j = 0; j < D.units_in_block; ++j, rr += rsr::kRecordWords) {
           const uint32_t meta = __builtin_bit_cast(uint32_t, rr[10]);
-          const int q = (int)(meta >> 16);
-          const unsigned w = meta & 0xffffu;
-          const AT tot = rr[9];
-#pragma unroll
-          for (int bit = 0; bit < rsr::kMaxK; ++bit) {
-            if (bit < p.k) {
-              AT t;
-              if (bit < rsr::kMaxWindowBits && bit < p.kw) t = rr[bit < rsr::kMaxWindowBits ? bit : 0];
-              else t = ((w >> (bit - p.kw)) & 1u) ? tot : (AT)0;
-              comb[0][bit] += (q == 0) ? t : (AT)0;
-              comb[1][bit] += (q == 1) ? t : (AT)0;
-            }
-          }
+          const AT t = rr[word];
+          const bool use = ((int)(meta >> 16) == q) && (bit < p.kw || (((meta & 0xffffu) >> (bit - p.kw)) & 1u));
+          sum += use ? t : (AT)0;
         }
+        const AT minus = __shfl(sum, lane + 16, 64);  // part 1 sits 16 lanes up
+        const AT res = sum - minus;                   // Proposition 2.1: v.B(1) - v.B(2)
         // value bit `bit` belongs to column k-1-bit of the block (first column most significant)
-        const int width = ((int)block == p.nblocks - 1) ? p.last_width : p.k;
-        AT mine = (AT)0;
-#pragma unroll
-        for (int bit = 0; bit < rsr::kMaxK; ++bit) {
-          if (bit < p.k) {
-            AT res = wave_sum_to_lane63<AT>(comb[0][bit]);
-            if (p.parts == 2) res -= wave_sum_to_lane63<AT>(comb[1][bit]);  // Proposition 2.1: v.B(1) - v.B(2)
-            res = lane63<AT>(res);
-            if (lane == p.k - 1 - bit) mine = res;
-          }
-        }
-        if (lane < width) outp[(int64_t)block * p.k + lane] = mine;
+        const int width = ((int)D.block == p.nblocks - 1) ? p.last_width : p.k;
+        const int col = p.k - 1 - bit;
+        if (lane < 16 && bit < p.k && col < width) outp[(int64_t)D.block * p.k + col] = res;
       }
-      ui = ui_next;
-      dw = dw_next;
+
+      // ---- take the unit after next and fetch its descriptor ----
+      uint32_t ui_nn = u_end, dw_nn = 0;
+      if (have_next) {
+        unsigned take = 0;
+        if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        ui_nn = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
+        if (ui_nn < u_end) dw_nn = unit_words[(size_t)ui_nn * 16 + (lane & 15)];
+      }
+      ui = ui_next; dw = dw_next; D = Dn;
+      ui_next = ui_nn; dw_next = dw_nn;
     }
     rb0 = rb1;
     __syncthreads();
@@ -457,7 +537,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   int nslot = 64;
   size_t ucap = std::max<size_t>(h->max_units_per_block, 256);
   int waves = h->waves;
-  auto total = [&](int w) { return vbytes + (size_t)w * win_bytes + ucap * rec_bytes + (size_t)nslot * 4 + 16; };
+  auto total = [&](int w) { return vbytes + (size_t)w * win_bytes + ucap * rec_bytes + (size_t)nslot * 4 + 16 + ((size_t)nslot + 1) * 4 + 12; };
   if (total(1) > h->lds_max && ucap > h->max_units_per_block) ucap = h->max_units_per_block;
   while (waves > 1 && total(waves) > h->lds_max) waves >>= 1;
   if (total(waves) > h->lds_max)
@@ -469,6 +549,8 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
   p.off_done = (uint32_t)(p.off_rec + ucap * rec_bytes);
   p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
+  p.off_bu = p.off_ctr + 16;
+  p.nunits = (int)h->nunits;
 
   // grid: about one (or two, if LDS allows) resident workgroups per compute unit in total
   int wg_per_cu = h->wg_per_cu > 0 ? h->wg_per_cu : (int)std::min<size_t>(2, h->lds_max / lds);
