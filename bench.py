@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg (profiling runs)")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check before timing")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
+                    help="also run N plain device copies of 256 MiB (a kernel of known traffic, used to "
+                         "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -161,6 +164,15 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     dev_ms = ev0.elapsed_time(ev1)
+
+    if args.copy_calibration > 0:
+        # reads 256 MiB and writes 256 MiB per copy; distinct buffers, larger than the last-level cache
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_per_step = wall * 1e3 / args.steps
     launch_us = dev_ms * 1e3 / args.steps

@@ -117,14 +117,14 @@ struct KArgs {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// 16-byte load of 8 row indices.  RSR_NT_LOADS selects non-temporal loads for the index stream.
+// The index streams are read once per product: non-temporal loads keep them from displacing
+// the small, reused data (descriptors, activations) in the caches.
 __device__ __forceinline__ uint4 load_entries(const uint4* p) {
-#ifdef RSR_NT_LOADS
   const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-#else
-  const u32x4 x = *reinterpret_cast<const u32x4*>(p);
-#endif
   return make_uint4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ uint32_t load_entry16(const uint16_t* p) {
+  return (uint32_t)__builtin_nontemporal_load(p);
 }
 
 // ---- wavefront sums with DPP (no LDS traffic).  The total ends up in lane 63. ----
@@ -294,7 +294,7 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
     for (int j = 0; j < kTChunk; ++j) {
       const int ct = (t0 + j < d.nt) ? desc_cnt(dwv, t0 + j) : 0;
       ti[j] = null_index;
-      if (lane < ct) ti[j] = *tp;
+      if (lane < ct) ti[j] = load_entry16(tp);
       tp += ct;
     }
   };
