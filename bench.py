@@ -32,6 +32,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a plain copy
+# of known size; summaries under profiles/).  Keyed by (workload, batch, dtype, regime); other
+# combinations report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("binary_16k", 1, "f32", "cold"): 58.58e6,   # profiles/rsr_matvec_f32_binary16k_b1_cold.md
+}
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache; the cold regime rotates over > 2x this
 
 
@@ -211,7 +218,7 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.batch, args.dtype, args.regime)),
             "algorithmic_bytes_per_launch": alg_bytes,
             "launch_us": launch_us,
         },
