@@ -472,7 +472,7 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
         // Lane (bit + 16 * part) adds up, over the block's units, "sum of u[j] over the values j
         // with bit `bit` set".  Bits below kw are in the unit records; a higher bit sees only
         // window totals (the remaining levels of the fold act on the windows' sums).
-        __atomic_thread_fence(__ATOMIC_ACQUIRE);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the records were written by this workgroup: no wider scope
         const int bit = lane & 15, q = lane >> 4;
         const AT* rr = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
         const int word = (bit < p.kw) ? bit : 9;
