@@ -118,9 +118,9 @@ typedef struct rsr_info_t {
   int32_t lo_bits, hi_bits; /* how the k value bits are split for the two-level fold */
   int64_t stored_rows;      /* row indices stored over all blocks and parts (value-0 rows left out) */
   int64_t segments;         /* stored groups of equal rows (long groups are cut into several) */
-  int64_t work_units;       /* scheduling units (up to 512 groups of up to 40 rows each) */
-  int64_t index_bytes;      /* packed permutation stream, padding included */
-  int64_t segment_bytes;    /* per-group value ids */
+  int64_t work_units;       /* scheduling units (part of the segments of 512 consecutive row values) */
+  int64_t index_bytes;      /* row indices of the packed permutation, padding included */
+  int64_t segment_bytes;    /* value ids of the segments, padding included */
   int64_t schedule_bytes;   /* unit descriptors and per-block unit ranges */
   int64_t table_bytes;      /* index_bytes + segment_bytes + schedule_bytes */
   int32_t device;           /* HIP device ordinal that holds the tables */
@@ -170,14 +170,12 @@ int rsr_host_export_block(const rsr_host_index *x, int part, int64_t block, int3
  * rsr_host_streams - read-only views of the packed streams exactly as they would be uploaded
  * (layout: see csrc/rsr_format.h).  Pointers are HOST memory owned by x and valid until
  * rsr_host_free.  Any output pointer may be NULL.
- *   entries / n_entries   uint16 row indices
- *   slots / n_slots       uint16 slot ids and overflow parents
- *   units / n_units       64-byte unit descriptors
+ *   stream / n_stream     uint16 elements of the unit streams (slot ids and row indices)
+ *   units / n_units       32-byte unit descriptors
  *   blk_unit              nblocks + 1 uint32 offsets into units
  */
-int rsr_host_streams(const rsr_host_index *x, const uint16_t **entries, int64_t *n_entries,
-                     const uint16_t **slots, int64_t *n_slots, const void **units, int64_t *n_units,
-                     const uint32_t **blk_unit);
+int rsr_host_streams(const rsr_host_index *x, const uint16_t **stream, int64_t *n_stream,
+                     const void **units, int64_t *n_units, const uint32_t **blk_unit);
 
 #ifdef __cplusplus
 }

@@ -42,15 +42,15 @@ class RsrInfo(ctypes.Structure):
         return {name: getattr(self, name) for name, _ in self._fields_}
 
 
-# numpy view of the 64-byte unit descriptors (csrc/rsr_format.h)
+# numpy view of the 32-byte unit descriptors (csrc/rsr_format.h)
 UNIT_DTYPE = np.dtype(
     [
-        ("entry_off", "<u4"), ("slot_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("npieces", "<u2"),
-        ("nt", "u1"), ("part", "u1"), ("nov", "u1"), ("nt_main", "u1"), ("units_in_block", "<u2"), ("main_granules", "<u2"),
-        ("cnt8", "u1", (40,)),
+        ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("nov", "u1"),
+        ("units_in_block", "<u2"), ("npos", "u1"), ("ngroups", "u1"),
+        ("hdr_lo", "<u4"), ("hdr_hi", "<u4"), ("nidx", "<u4"), ("npieces", "<u4"),
     ]
 )
-assert UNIT_DTYPE.itemsize == 64
+assert UNIT_DTYPE.itemsize == 32
 
 
 def lib_path() -> str:
@@ -99,7 +99,7 @@ def load() -> ctypes.CDLL:
     L.rsr_host_info.restype = ci
     L.rsr_host_export_block.argtypes = [vp, ci, i64, vp, vp]
     L.rsr_host_export_block.restype = ci
-    L.rsr_host_streams.argtypes = [vp] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 3 + [ctypes.POINTER(vp)]
+    L.rsr_host_streams.argtypes = [vp] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 2 + [ctypes.POINTER(vp)]
     L.rsr_host_streams.restype = ci
     _lib = L
     return L
@@ -201,12 +201,12 @@ def rsr_host_export_block(x: int, part: int, block: int) -> Tuple[np.ndarray, np
 
 
 def rsr_host_streams(x: int) -> dict:
-    """Copies of the packed streams as numpy arrays: entries, slots, units (structured), blk_unit."""
+    """Copies of the packed streams as numpy arrays: stream (uint16), units (structured), blk_unit."""
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
-    pe, ps, pu, pb = vp(), vp(), vp(), vp()
-    ne, ns, nu = i64(), i64(), i64()
-    _check(load().rsr_host_streams(x, ctypes.byref(pe), ctypes.byref(ne), ctypes.byref(ps), ctypes.byref(ns),
-                                   ctypes.byref(pu), ctypes.byref(nu), ctypes.byref(pb)))
+    pe, pu, pb = vp(), vp(), vp()
+    ne, nu = i64(), i64()
+    _check(load().rsr_host_streams(x, ctypes.byref(pe), ctypes.byref(ne), ctypes.byref(pu), ctypes.byref(nu),
+                                   ctypes.byref(pb)))
     info = rsr_host_info(x)
 
     def view(ptr, count, dtype):
@@ -217,8 +217,7 @@ def rsr_host_streams(x: int) -> dict:
         return np.frombuffer(buf, dtype=dtype, count=count).copy()
 
     return {
-        "entries": view(pe, ne.value, np.uint16),
-        "slots": view(ps, ns.value, np.uint16),
+        "stream": view(pe, ne.value, np.uint16),
         "units": view(pu, nu.value, UNIT_DTYPE),
         "blk_unit": view(pb, info.nblocks + 1, np.uint32),
     }

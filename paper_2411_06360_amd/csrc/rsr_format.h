@@ -10,31 +10,36 @@
 //     values are shifted left by (k - width).  Rows with value 0 add nothing to the block
 //     (row 0 of Bin_[k] is zero) and are not stored.
 //   * The 2^k values of a block are cut into windows of 2^kw consecutive values
-//     (kw = min(k, 9)).  One wavefront handles one window at a time: the segment sums u[j] of
-//     the window live in that wavefront's private LDS slice, where the low kw levels of the
-//     RSR++ fold are taken; the remaining k - kw levels only need each window's total.
-//   * Inside a window every group of equal rows ("segment") is a piece.  Pieces are ranked by
-//     descending length; lane l of the wavefront owns ranks 8l .. 8l+7 and keeps one
-//     accumulator per rank.  Diagonal t of the window lists, for ranks 0 .. cnt_t-1 (the pieces
-//     longer than t), the t-th row of each piece.  Diagonals come in two tiers:
-//       - wide diagonals (t < nt_main): padded to a multiple of 8 with the null row index `rows`
-//         (which reads a zero kept behind the activation vector in LDS).  A lane reads its 8
-//         entries with one 16-byte load; a wavefront reads one contiguous KB.
-//       - tail diagonals (t >= nt_main, the first diagonal with at most 64 pieces left): stored
-//         back to back without padding; lane l reads the single entry of rank l and adds it to a
-//         ninth accumulator, which is merged into the rank's slot afterwards.  This keeps the few
-//         long segments from costing a full 8-gather step each.  The tail region as a whole is
-//         padded to 16 bytes.
-//   * A segment longer than kMaxDiag rows is cut into several pieces; the first keeps the
-//     segment's slot in the window, the others get overflow slots whose parent value is listed
-//     behind the unit's slot ids.  A window with more pieces than one unit can hold continues
-//     in further units; unit results add up because the fold is linear in u.
+//     (kw = min(k, 9)).  One wavefront handles one work unit at a time: (part of) a window, whose
+//     segment sums u[j] live in that wavefront's private LDS slice, where the low kw levels of
+//     the RSR++ fold are taken; the remaining k - kw levels only need each window's total.  A
+//     window may be spread over several units: their results add up because the fold is
+//     linear in u.
+//   * Every set of equal rows ("segment") of the window is cut into pieces of at most T rows (T is
+//     chosen per window so that the stream gets shortest).  Pieces are ranked by descending
+//     length; ranks 64i .. 64i+63 form group i, one piece per lane.  Inside a unit the first
+//     piece of a segment delivers its sum to the segment's own slot of the window; every further
+//     piece of that segment gets an overflow slot of its own, and the unit lists the segment
+//     value ("parent") of each overflow slot: the fold adds an overflow sum wherever its parent's
+//     bits say so, which is the same as adding it to the parent first.
+//   * The unit's stream is a sequence of positions; a position holds one uint16 per lane.  It
+//     starts with 0, 1 or 2 parent positions (lane x of parent position c: the parent of overflow
+//     slot 64c + x).  Then the groups follow: a header position and n index positions (n = the
+//     group's longest piece).  The header names, per lane, the window slot that receives the
+//     lane's sum for the group; lanes without a piece name a dummy slot.  An index position holds
+//     the next row of each lane's piece, or the null row index `rows` (which reads a zero kept
+//     behind the activation vector in LDS) once the piece is exhausted.  A bit mask in the
+//     descriptor marks the header positions.  The number of positions is even (a null position is
+//     appended if needed) and at most kMaxPositions.
+//   * In memory a lane's uint16s of 8 consecutive positions are adjacent: positions 8g .. 8g+7
+//     form a granule of 64 x 16 bytes (lane-major), read with one 16-byte load per lane.  The
+//     positions behind the last full granule are stored as rows of dwords (two positions per
+//     lane, 256 bytes per row).  A unit's stream starts on a 256-byte boundary.
+//   * Within a unit no two pieces deliver to the same slot (plain stores, no read-modify-write).
 //
 // Streams on the device:
-//   entries   uint16  row indices, unit after unit, diagonal after diagonal
-//   slots     uint16  per unit: slot id of every rank (padded to 8 with the dummy slot), then the
-//                     parent values of its overflow slots (padded to 8)
-//   units     Unit    64-byte descriptors, ordered by block, then part, then window
+//   stream    bytes   unit streams, back to back
+//   units     Unit    32-byte descriptors, ordered by block
 //   blk_unit  uint32  nblocks+1 offsets into `units`
 #ifndef RSR_FORMAT_H_
 #define RSR_FORMAT_H_
@@ -44,35 +49,36 @@
 namespace rsr {
 
 constexpr int kLanes = 64;             // wavefront width
-constexpr int kPerLane = 8;            // ranks (accumulators) per lane = uint16 entries per 16-byte load
-constexpr int kTileRanks = kLanes * kPerLane;  // 512 pieces per unit
 constexpr int kMaxWindowBits = 9;      // window = 2^kw values, kw = min(k, 9)
 constexpr int kWindow = 1 << kMaxWindowBits;   // LDS slots of a window (always allocated in full)
-constexpr int kDummySlots = 8;         // slot ids kWindow .. kWindow+7 swallow padding ranks
-constexpr int kMaxOverflow = 64;       // overflow slots per unit (ids kWindow+8 .. kWindow+71)
+constexpr int kDummySlots = 8;         // slot ids kWindow .. kWindow+7 swallow lanes without a piece
+constexpr int kMaxOverflow = 128;      // overflow slots per unit (ids kOverflowBase ..)
 constexpr int kOverflowBase = kWindow + kDummySlots;
-constexpr int kWindowSlots = kOverflowBase + kMaxOverflow;  // 584 accumulators per wavefront
-constexpr int kMaxDiag = 40;           // diagonals (rows per piece) per unit
+constexpr int kWindowSlots = kOverflowBase + kMaxOverflow;  // 648 accumulators per wavefront
+constexpr int kGranulePositions = 8;   // positions per 16-byte granule
+constexpr int kMaxGranules = 6;        // full granules of a unit at most
+constexpr int kMaxPositions = kMaxGranules * kGranulePositions;  // 48
+constexpr int kPositionBytes = kLanes * 2;    // 128
+constexpr int kStreamAlign = 256;      // unit streams start on multiples of this
 constexpr int kMaxK = 16;
-constexpr int kTailRanks = 64;         // a tail diagonal has at most one entry per lane
 constexpr int kMaxRows = 65534;        // 65535 values of uint16 minus the null index
 constexpr int kRecordWords = 16;       // per-unit result record in LDS: 9 low-bit sums, total, meta
 
 struct alignas(16) Unit {
-  uint32_t entry_off;  // start of the unit's entries, in 16-byte granules
-  uint32_t slot_off;   // start of the unit's slot ids, in 16-byte granules
-  uint32_t block;      // column block
-  uint16_t window;     // window index inside the block: value >> kw
-  uint16_t npieces;    // ranks in use, <= 512
-  uint8_t nt;          // diagonals, <= kMaxDiag
-  uint8_t part;        // 0: B(1) (or binary B), 1: B(2)
-  uint8_t nov;         // overflow slots in use, <= kMaxOverflow
-  uint8_t nt_main;     // wide diagonals; diagonals nt_main .. nt-1 form the tail
+  uint32_t stream_off;      // start of the unit's stream, in multiples of kStreamAlign bytes
+  uint32_t block;           // column block
+  uint16_t window;          // window index inside the block: value >> kw
+  uint8_t part;             // 0: B(1) (or binary B), 1: B(2)
+  uint8_t nov;              // overflow slots in use, <= kMaxOverflow; parent positions = ceil(nov / 64)
   uint16_t units_in_block;  // units of this unit's column block (all parts and windows)
-  uint16_t main_granules;   // 16-byte granules of the wide diagonals = offset of the tail region
-  uint8_t cnt8[kMaxDiag];   // wide diagonal: active lanes (16-byte granules); tail diagonal: entries
+  uint8_t npos;             // positions in the stream: even, <= kMaxPositions
+  uint8_t ngroups;          // groups = header positions
+  uint32_t hdr_lo;          // bit p: position p is a header (positions 0..31)
+  uint32_t hdr_hi;          // positions 32..47
+  uint32_t nidx;            // real (non-null) row indices in the unit
+  uint32_t npieces;         // pieces in the unit
 };
-static_assert(sizeof(Unit) == 64, "unit descriptor must be 64 bytes");
+static_assert(sizeof(Unit) == 32, "unit descriptor must be 32 bytes");
 
 }  // namespace rsr
 #endif  // RSR_FORMAT_H_

@@ -65,10 +65,10 @@ struct rsr_handle {
   int k = 0, kw = 0, parts = 0, last_width = 0;
   uint32_t max_units_per_block = 0;
   int64_t stored_rows = 0, segments = 0, nunits = 0;
-  size_t entry_bytes = 0, slot_bytes = 0, unit_bytes = 0, blk_bytes = 0;
+  int64_t header_positions = 0;
+  size_t stream_bytes = 0, unit_bytes = 0, blk_bytes = 0;
   // device tables
-  void* d_entries = nullptr;
-  void* d_slots = nullptr;
+  void* d_stream = nullptr;
   void* d_units = nullptr;
   void* d_blk_unit = nullptr;
   // tuning (environment overrides read at preprocess time)
@@ -94,8 +94,8 @@ void fill_info(const rsr::Packed& P, rsr_info_t* info) {
   info->nblocks = P.nblocks; info->last_block_width = P.last_width;
   info->lo_bits = P.kw; info->hi_bits = P.k - P.kw;
   info->stored_rows = P.stored_rows; info->segments = P.segments; info->work_units = (int64_t)P.units.size();
-  info->index_bytes = (int64_t)(P.entries.size() * sizeof(uint16_t));
-  info->segment_bytes = (int64_t)(P.slots.size() * sizeof(uint16_t));
+  info->segment_bytes = P.header_positions * rsr::kPositionBytes;
+  info->index_bytes = (int64_t)(P.stream.size() * sizeof(uint16_t)) - info->segment_bytes;
   info->schedule_bytes = (int64_t)(P.units.size() * sizeof(rsr::Unit) + P.blk_unit.size() * sizeof(uint32_t));
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
   info->device = -1; info->compute_units = 0;
@@ -117,14 +117,13 @@ struct KArgs {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// The index streams are read once per product: non-temporal loads keep them from displacing
-// the small, reused data (descriptors, activations) in the caches.
-__device__ __forceinline__ uint4 load_entries(const uint4* p) {
-  const u32x4 x = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-  return make_uint4(x.x, x.y, x.z, x.w);
+// The index stream is read once per product: non-temporal loads keep it from displacing the
+// small, reused data (descriptors, activations) in the caches.
+__device__ __forceinline__ u32x4 load_granule(const unsigned char* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
-__device__ __forceinline__ uint32_t load_entry16(const uint16_t* p) {
-  return (uint32_t)__builtin_nontemporal_load(p);
+__device__ __forceinline__ uint32_t load_pair(const unsigned char* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
 }
 
 // ---- wavefront sums with DPP (no LDS traffic).  The total ends up in lane 63. ----
@@ -147,10 +146,6 @@ __device__ __forceinline__ AT wave_sum_to_lane63(AT x) {
   y += dpp_get<0x142, 0xa, 0xf>(y);         // row_bcast:15 into rows 1 and 3
   y += dpp_get<0x143, 0xc, 0xf>(y);         // row_bcast:31 into rows 2 and 3 -> lane 63 holds all
   return y;
-}
-template <typename AT>
-__device__ __forceinline__ AT lane63(AT x) {
-  return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), 63));
 }
 
 template <typename AT>
@@ -190,61 +185,123 @@ template <typename VT> struct Acc;
 template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
 
-template <typename VT, typename AT>
-__device__ __forceinline__ void gather8(const VT* __restrict__ vl, const uint4& e, AT (&acc)[8]) {
-  acc[0] += (AT)vl[e.x & 0xffffu];
-  acc[1] += (AT)vl[e.x >> 16];
-  acc[2] += (AT)vl[e.y & 0xffffu];
-  acc[3] += (AT)vl[e.y >> 16];
-  acc[4] += (AT)vl[e.z & 0xffffu];
-  acc[5] += (AT)vl[e.z >> 16];
-  acc[6] += (AT)vl[e.w & 0xffffu];
-  acc[7] += (AT)vl[e.w >> 16];
+// ---- the stream positions of a lane unit, eight (one granule) or two (one dword) at a time ----
+// Per position and lane the stream holds a uint16 x.  At a header position (bit set in `hb`) the
+// running sum `a` of the group that ends here goes to the window slot the lane was given at the
+// group's own header (LDS byte address `sa`), x names the next slot and the sum restarts; at any
+// other position the activation with row index x is added.  All eight gathers are issued before
+// the first sum so that their latencies overlap.  Written in assembly because the compiler turns
+// the per-position choice into long chains of scalar bookkeeping: here a position costs one
+// address extraction, one LDS read, one bit test, one branch and one add.
+//   float activations:  LDS byte address of row x = 4 * x (the vector sits at LDS offset 0)
+//   int8 activations:   LDS byte address of row x = x
+#define RSR_X4_LO(d, w) "v_lshlrev_b32_sdwa " d ", 2, " w " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n"
+#define RSR_X4_HI(d, w) "v_lshlrev_b32_sdwa " d ", 2, " w " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n"
+#define RSR_X1_LO(d, w) "v_and_b32 " d ", 0xffff, " w "\n"
+#define RSR_X1_HI(d, w) "v_lshrrev_b32 " d ", 16, " w "\n"
+#define RSR_POS(q, cnt, ADD) \
+  "s_bitcmp1_b32 %[hb], " #q "\n s_cbranch_scc1 .Lh" #q "_%=\n s_waitcnt lgkmcnt(" #cnt ")\n " ADD " %[a], %[a], %[t" #q "]\n .Lc" #q "_%=:\n"
+#define RSR_HDR_F32(q) \
+  ".Lh" #q "_%=:\n ds_write_b32 %[sa], %[a]\n v_add_u32 %[sa], %[wb], %[s" #q "]\n v_mov_b32 %[a], 0\n s_branch .Lc" #q "_%=\n"
+#define RSR_HDR_I8(q) \
+  ".Lh" #q "_%=:\n ds_write_b32 %[sa], %[a]\n v_lshl_add_u32 %[sa], %[s" #q "], 2, %[wb]\n v_mov_b32 %[a], 0\n s_branch .Lc" #q "_%=\n"
+
+__device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, float& a,
+                                             uint32_t& sa, uint32_t wb, const float*) {
+  uint32_t s0, s1, s2, s3, s4, s5, s6, s7;
+  float t0, t1, t2, t3, t4, t5, t6, t7;
+  asm volatile(
+      RSR_X4_LO("%[s0]", "%[w0]") RSR_X4_HI("%[s1]", "%[w0]") RSR_X4_LO("%[s2]", "%[w1]") RSR_X4_HI("%[s3]", "%[w1]")
+      RSR_X4_LO("%[s4]", "%[w2]") RSR_X4_HI("%[s5]", "%[w2]") RSR_X4_LO("%[s6]", "%[w3]") RSR_X4_HI("%[s7]", "%[w3]")
+      "ds_read_b32 %[t0], %[s0]\n ds_read_b32 %[t1], %[s1]\n ds_read_b32 %[t2], %[s2]\n ds_read_b32 %[t3], %[s3]\n"
+      "ds_read_b32 %[t4], %[s4]\n ds_read_b32 %[t5], %[s5]\n ds_read_b32 %[t6], %[s6]\n ds_read_b32 %[t7], %[s7]\n"
+      RSR_POS(0, 7, "v_add_f32") RSR_POS(1, 6, "v_add_f32") RSR_POS(2, 5, "v_add_f32") RSR_POS(3, 4, "v_add_f32")
+      RSR_POS(4, 3, "v_add_f32") RSR_POS(5, 2, "v_add_f32") RSR_POS(6, 1, "v_add_f32") RSR_POS(7, 0, "v_add_f32")
+      "s_branch .Lend_%=\n"
+      RSR_HDR_F32(0) RSR_HDR_F32(1) RSR_HDR_F32(2) RSR_HDR_F32(3) RSR_HDR_F32(4) RSR_HDR_F32(5) RSR_HDR_F32(6) RSR_HDR_F32(7)
+      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
+      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3), [s4] "=&v"(s4),
+        [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
+        [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
+      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
+      : "scc", "memory");
+}
+__device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, float& a, uint32_t& sa, uint32_t wb, const float*) {
+  uint32_t s0, s1;
+  float t0, t1;
+  asm volatile(
+      RSR_X4_LO("%[s0]", "%[w0]") RSR_X4_HI("%[s1]", "%[w0]")
+      "ds_read_b32 %[t0], %[s0]\n ds_read_b32 %[t1], %[s1]\n"
+      RSR_POS(0, 1, "v_add_f32") RSR_POS(1, 0, "v_add_f32")
+      "s_branch .Lend_%=\n"
+      RSR_HDR_F32(0) RSR_HDR_F32(1)
+      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
+      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0)
+      : "scc", "memory");
+}
+__device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, int32_t& a,
+                                             uint32_t& sa, uint32_t wb, const int8_t*) {
+  uint32_t s0, s1, s2, s3, s4, s5, s6, s7;
+  int32_t t0, t1, t2, t3, t4, t5, t6, t7;
+  asm volatile(
+      RSR_X1_LO("%[s0]", "%[w0]") RSR_X1_HI("%[s1]", "%[w0]") RSR_X1_LO("%[s2]", "%[w1]") RSR_X1_HI("%[s3]", "%[w1]")
+      RSR_X1_LO("%[s4]", "%[w2]") RSR_X1_HI("%[s5]", "%[w2]") RSR_X1_LO("%[s6]", "%[w3]") RSR_X1_HI("%[s7]", "%[w3]")
+      "ds_read_i8 %[t0], %[s0]\n ds_read_i8 %[t1], %[s1]\n ds_read_i8 %[t2], %[s2]\n ds_read_i8 %[t3], %[s3]\n"
+      "ds_read_i8 %[t4], %[s4]\n ds_read_i8 %[t5], %[s5]\n ds_read_i8 %[t6], %[s6]\n ds_read_i8 %[t7], %[s7]\n"
+      RSR_POS(0, 7, "v_add_u32") RSR_POS(1, 6, "v_add_u32") RSR_POS(2, 5, "v_add_u32") RSR_POS(3, 4, "v_add_u32")
+      RSR_POS(4, 3, "v_add_u32") RSR_POS(5, 2, "v_add_u32") RSR_POS(6, 1, "v_add_u32") RSR_POS(7, 0, "v_add_u32")
+      "s_branch .Lend_%=\n"
+      RSR_HDR_I8(0) RSR_HDR_I8(1) RSR_HDR_I8(2) RSR_HDR_I8(3) RSR_HDR_I8(4) RSR_HDR_I8(5) RSR_HDR_I8(6) RSR_HDR_I8(7)
+      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
+      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3), [s4] "=&v"(s4),
+        [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
+        [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
+      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
+      : "scc", "memory");
+}
+__device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, uint32_t& sa, uint32_t wb, const int8_t*) {
+  uint32_t s0, s1;
+  int32_t t0, t1;
+  asm volatile(
+      RSR_X1_LO("%[s0]", "%[w0]") RSR_X1_HI("%[s1]", "%[w0]")
+      "ds_read_i8 %[t0], %[s0]\n ds_read_i8 %[t1], %[s1]\n"
+      RSR_POS(0, 1, "v_add_u32") RSR_POS(1, 0, "v_add_u32")
+      "s_branch .Lend_%=\n"
+      RSR_HDR_I8(0) RSR_HDR_I8(1)
+      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
+      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0)
+      : "scc", "memory");
 }
 
-// Diagonals fetched ahead of their gathers (sized so that the kernel keeps 16 wavefronts per
-// compute unit, i.e. 128 registers, without spilling).
-constexpr int kChunk = 6;   // wide diagonals: 4 registers each
-constexpr int kTChunk = 8;  // tail diagonals: 1 register each
-
-// Descriptor word w of the unit whose 16 dwords sit in lanes 0..15 of `dw`.
-__device__ __forceinline__ uint32_t desc_word(uint32_t dw, int w) {
-  return (uint32_t)__builtin_amdgcn_readlane((int)dw, w);
-}
-// Byte t of the cnt8 array, which starts at descriptor word 6.
-__device__ __forceinline__ int desc_cnt(uint32_t dw, int t) {
-  return (int)((desc_word(dw, 6 + (t >> 2)) >> ((t & 3) * 8)) & 0xffu);
-}
-
-// The scalar fields of a unit descriptor (wavefront-uniform).
+// The scalar fields of a unit descriptor (wavefront-uniform); its 8 dwords sit in lanes 0..7 of dw.
 struct Desc {
-  uint32_t entry_off, slot_off, block, main_granules;
-  int window, npieces, nt, part, nov, nt_main, units_in_block, nsl, ntail;
+  uint32_t stream_off, block, hdr_lo, hdr_hi;
+  int window, part, nov, units_in_block, npos;
 };
 __device__ __forceinline__ Desc decode(uint32_t dw) {
   Desc d;
-  d.entry_off = desc_word(dw, 0);
-  d.slot_off = desc_word(dw, 1);
-  d.block = desc_word(dw, 2);
-  const uint32_t w3 = desc_word(dw, 3), w4 = desc_word(dw, 4), w5 = desc_word(dw, 5);
-  d.window = (int)(w3 & 0xffffu);
-  d.npieces = (int)(w3 >> 16);
-  d.nt = (int)(w4 & 0xffu);
-  d.part = (int)((w4 >> 8) & 0xffu);
-  d.nov = (int)((w4 >> 16) & 0xffu);
-  d.nt_main = (int)(w4 >> 24);
-  d.units_in_block = (int)(w5 & 0xffffu);
-  d.main_granules = w5 >> 16;
-  d.nsl = (d.npieces + 7) >> 3;                                     // lanes that own pieces
-  d.ntail = (d.nt_main < d.nt) ? desc_cnt(dw, d.nt_main) : 0;       // ranks that continue into the tail
+  d.stream_off = (uint32_t)__builtin_amdgcn_readlane((int)dw, 0);
+  d.block = (uint32_t)__builtin_amdgcn_readlane((int)dw, 1);
+  const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 2), w3 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 3);
+  d.window = (int)(w2 & 0xffffu);
+  d.part = (int)((w2 >> 16) & 0xffu);
+  d.nov = (int)(w2 >> 24);
+  d.units_in_block = (int)(w3 & 0xffffu);
+  d.npos = (int)((w3 >> 16) & 0xffu);
+  d.hdr_lo = (uint32_t)__builtin_amdgcn_readlane((int)dw, 4);
+  d.hdr_hi = (uint32_t)__builtin_amdgcn_readlane((int)dw, 5);
   return d;
 }
 
+constexpr int NG = rsr::kMaxGranules;
+
 template <typename VT>
 __global__ void __launch_bounds__(1024)
-rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ slots,
-                  const uint32_t* __restrict__ unit_words, const uint32_t* __restrict__ blk_unit,
-                  const VT* __restrict__ vin, typename Acc<VT>::type* __restrict__ out, const KArgs p) {
+rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
+                  const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
+                  typename Acc<VT>::type* __restrict__ out, const KArgs p) {
   using AT = typename Acc<VT>::type;
   extern __shared__ __align__(16) unsigned char lds[];
   VT* vl = reinterpret_cast<VT*>(lds);
@@ -264,50 +321,37 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
   const int blk_end = (int)((int64_t)(g + 1) * p.nblocks / p.g1);
   if (blk_begin >= blk_end) return;
 
-  AT* win = reinterpret_cast<AT*>(lds + p.off_win) + wave * rsr::kWindowSlots;
+  const uint32_t winbase = p.off_win + (uint32_t)wave * (rsr::kWindowSlots * 4);
+  AT* win = reinterpret_cast<AT*>(lds + winbase);
   AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
   unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
   unsigned* ctr = reinterpret_cast<unsigned*>(lds + p.off_ctr);
   uint32_t* bu = reinterpret_cast<uint32_t*>(lds + p.off_bu);  // first unit of the round's blocks
   AT* outp = out + (int64_t)b * p.cols;
-  const uint32_t null_index = (uint32_t)p.rows;
+  const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
 
-  // Loads of one unit into registers.  Wide diagonals: one 16-byte granule per active lane;
-  // tail diagonals: one entry per active lane; then the slot ids.
-  uint4 e[kChunk];
-  int c[kChunk];
-  uint32_t ti[kTChunk];
-  uint4 sl = make_uint4(0, 0, 0, 0);
-  uint32_t tslot = 0;
-  const uint4* ep = entries;
-  const uint16_t* tp = reinterpret_cast<const uint16_t*>(entries);
-  auto issue_wide = [&](const Desc& d, uint32_t dwv, int t0) {
+  // Two register buffers: while one unit is summed from one, the next unit's stream arrives in the
+  // other.  Every unit issues the same number of loads (the ones it does not need read the first
+  // bytes of the stream, which stay cached), so that the wait counts between units are exact and a
+  // wait for the current unit never waits for the next one.
+  uint32_t eA[NG][4], eB[NG][4];
+  uint32_t tA[3], tB[3];  // positions behind the last full granule: up to three rows of dwords
+  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
+    const int full = npos >> 3;
+    const unsigned char* us = stream + (size_t)stream_off * rsr::kStreamAlign;
 #pragma unroll
-    for (int j = 0; j < kChunk; ++j) {
-      c[j] = (t0 + j < d.nt_main) ? desc_cnt(dwv, t0 + j) : 0;
-      if (lane < c[j]) e[j] = load_entries(ep);
-      ep += c[j];
+    for (int gq = 0; gq < NG; ++gq) {
+      const unsigned char* src = (gq < full) ? us + gq * 1024 : stream;
+      const u32x4 x = load_granule(src + lane16);
+      e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
     }
-  };
-  auto issue_tail = [&](const Desc& d, uint32_t dwv, int t0) {
+    const int pairs = (npos & 7) >> 1;
+    const unsigned char* ut = us + (size_t)full * 1024;
 #pragma unroll
-    for (int j = 0; j < kTChunk; ++j) {
-      const int ct = (t0 + j < d.nt) ? desc_cnt(dwv, t0 + j) : 0;
-      ti[j] = null_index;
-      if (lane < ct) ti[j] = load_entry16(tp);
-      tp += ct;
+    for (int j = 0; j < 3; ++j) {
+      const unsigned char* src = (j < pairs) ? ut + j * 256 : stream;
+      et[j] = load_pair(src + lane4);
     }
-  };
-  auto issue_slots = [&](const Desc& d) {
-    if (lane < d.nsl) sl = slots[d.slot_off + lane];
-    if (lane < d.ntail) tslot = reinterpret_cast<const uint16_t*>(slots + d.slot_off)[lane];
-  };
-  auto issue_unit = [&](const Desc& d, uint32_t dwv) {
-    ep = entries + d.entry_off + lane;
-    issue_wide(d, dwv, 0);
-    tp = reinterpret_cast<const uint16_t*>(entries + d.entry_off + d.main_granules) + lane;
-    issue_tail(d, dwv, d.nt_main);
-    issue_slots(d);
   };
 
   bool first_round = true;
@@ -320,11 +364,10 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
     }
     if (tid < p.nslot) done[tid] = 0;
     if (tid == 0) *ctr = (unsigned)nwaves;  // the first unit of every wavefront is fixed: u_begin + wave
-    // first unit of this wavefront: descriptor and loads go out before the barrier
+    // first unit of this wavefront: descriptor and stream loads go out before the barrier
     const uint32_t u_begin = blk_unit[rb0];
-    uint32_t ui = u_begin + (uint32_t)wave;
-    uint32_t dw = 0;
-    if (ui < (uint32_t)p.nunits) dw = unit_words[(size_t)ui * 16 + (lane & 15)];
+    const uint32_t guess = u_begin + (uint32_t)wave;
+    uint32_t dw = unit_words[(size_t)(guess < (uint32_t)p.nunits ? guess : 0u) * 8 + (lane & 7)];
     if (first_round) {
       // stage the activation vector; vl[rows] = 0 serves the null row index
       const VT* __restrict__ v = vin + (int64_t)b * p.rows;
@@ -338,7 +381,7 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
       first_round = false;
     }
     Desc D = decode(dw);
-    if (ui < (uint32_t)p.nunits) issue_unit(D, dw);
+    issue(D.stream_off, D.npos, eA, tA);
     __syncthreads();
     int nblk;
     {
@@ -348,79 +391,62 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
       if (nblk < 1) nblk = 1;  // a single block always fits: ucap >= the largest block
     }
     const int rb1 = rb0 + nblk;
-    const uint32_t u_end = bu[nblk];
+    const uint32_t n_tot = bu[nblk] - u_begin;  // units of this round, numbered 0 .. n_tot-1
 
-    // next unit: taken from the workgroup's counter; its descriptor is fetched a unit ahead
-    uint32_t ui_next = u_end, dw_next = 0;
-    if (ui < u_end) {
-      unsigned take = 0;
-      if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      ui_next = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
-      if (ui_next < u_end) dw_next = unit_words[(size_t)ui_next * 16 + (lane & 15)];
-    }
+    // unit index pipeline: ix is summed now, ix1 is the one whose stream is loaded meanwhile, and
+    // the descriptor of ix2 is fetched; units come from the workgroup's counter
+    auto take = [&]() {
+      unsigned t = 0;
+      if (lane == 0) t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      return (uint32_t)__builtin_amdgcn_readfirstlane(t);
+    };
+    auto fetch_desc = [&](uint32_t ixq) {  // always one load; past the end it reads unit 0 (unused)
+      return unit_words[(size_t)(ixq < n_tot ? u_begin + ixq : 0u) * 8 + (lane & 7)];
+    };
+    uint32_t ix = (uint32_t)wave;
+    uint32_t ix1 = (ix < n_tot) ? take() : n_tot;
+    uint32_t dw1 = fetch_desc(ix1);
 
-    while (ui < u_end) {
-      // ---- step 1: segmented sums (Eq. SS2), one accumulator per piece ----
-      AT acc[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] = (AT)0;
-      for (int t0 = 0;;) {
-#pragma unroll
-        for (int j = 0; j < kChunk; ++j)
-          if (lane < c[j]) gather8<VT, AT>(vl, e[j], acc);
-        t0 += kChunk;
-        if (t0 >= D.nt_main) break;
-        issue_wide(D, dw, t0);  // more than kChunk wide diagonals: long segments only
-      }
-      // the wide registers are free again: the next unit's wide diagonals go out now
-      Desc Dn = D;
-      const bool have_next = ui_next < u_end;
-      if (have_next) {
-        Dn = decode(dw_next);
-        ep = entries + Dn.entry_off + lane;
-        issue_wide(Dn, dw_next, 0);
-      }
-      // tail: rank l is served by lane l; lanes past a diagonal's end read the zero behind v
-      AT tacc = (AT)0;
-      if (D.nt_main < D.nt) {
-        for (int t0 = D.nt_main;;) {
-#pragma unroll
-          for (int j = 0; j < kTChunk; ++j) tacc += (AT)vl[ti[j]];
-          t0 += kTChunk;
-          if (t0 >= D.nt) break;
-          issue_tail(D, dw, t0);
-        }
-      }
-      if (have_next) {
-        tp = reinterpret_cast<const uint16_t*>(entries + Dn.entry_off + Dn.main_granules) + lane;
-        issue_tail(Dn, dw_next, Dn.nt_main);
-      }
+    // One unit from buffer (e, et); the next unit's stream goes into (en, etn) first.
+    auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[3], uint32_t (&en)[NG][4], uint32_t (&etn)[3]) {
+      const uint32_t ix2 = (ix1 < n_tot) ? take() : n_tot;
+      const uint32_t dw2 = fetch_desc(ix2);
+      Desc D1 = decode(dw1);
+      if (ix1 >= n_tot) D1.npos = 0;
+      issue(D1.stream_off, D1.npos, en, etn);
 
-      // ---- segment sums into the window (u of Algorithm 2, this window's slice) ----
+      // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
         uint4* w16 = reinterpret_cast<uint4*>(win);
         for (int i = lane; i < rsr::kWindowSlots / 4; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
       }
-      if (lane < D.nsl) {
-        win[sl.x & 0xffffu] = acc[0];
-        win[sl.x >> 16] = acc[1];
-        win[sl.y & 0xffffu] = acc[2];
-        win[sl.y >> 16] = acc[3];
-        win[sl.z & 0xffffu] = acc[4];
-        win[sl.z >> 16] = acc[5];
-        win[sl.w & 0xffffu] = acc[6];
-        win[sl.w >> 16] = acc[7];
+      AT a = (AT)0;
+      uint32_t sa = winbase + (uint32_t)(rsr::kWindow + (lane & (rsr::kDummySlots - 1))) * 4u;  // nothing to deliver yet
+      const int full = D.npos >> 3;
+#pragma unroll
+      for (int gq = 0; gq < NG; ++gq) {
+        if (gq < full) {
+          const uint32_t hb = ((gq < 4 ? D.hdr_lo : D.hdr_hi) >> (8 * (gq & 3))) & 0xffu;
+          granule_step(hb, e[gq][0], e[gq][1], e[gq][2], e[gq][3], a, sa, winbase, vl);
+        }
       }
-      if (lane < D.ntail) win[tslot] += tacc;  // distinct ranks have distinct slots: no two lanes collide
-      if (have_next) issue_slots(Dn);
+      {
+        const int pairs = (D.npos & 7) >> 1;
+        const uint64_t hdr = ((uint64_t)D.hdr_hi << 32) | D.hdr_lo;
+        const uint32_t tm = (uint32_t)(hdr >> (8 * full));
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+          if (j < pairs) pair_step((tm >> (2 * j)) & 3u, et[j], a, sa, winbase, vl);
+      }
+      *reinterpret_cast<AT*>(lds + sa) = a;  // the last group
 
       // ---- step 2: the low levels of the RSR++ fold on this window ----
       // lane l holds the values 8l .. 8l+7 of the window: three levels in registers ...
       AT u[8];
       {
-        const uint4 a = reinterpret_cast<const uint4*>(win)[2 * lane];
-        const uint4 cc = reinterpret_cast<const uint4*>(win)[2 * lane + 1];
-        const uint32_t raw[8] = {a.x, a.y, a.z, a.w, cc.x, cc.y, cc.z, cc.w};
+        const uint4 x0 = reinterpret_cast<const uint4*>(win)[2 * lane];
+        const uint4 x1 = reinterpret_cast<const uint4*>(win)[2 * lane + 1];
+        const uint32_t raw[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
 #pragma unroll
         for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
       }
@@ -437,18 +463,23 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
       for (int beta = 0; beta < 4; ++beta) vals[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
       vals[7] = x;
       AT ov7 = (AT)0, ov8 = (AT)0, ovt = (AT)0;
-      if (D.nov > 0) {  // pieces cut off long segments: add them under their parent's value
-        AT val = (AT)0;
-        unsigned par = 0;
-        if (lane < D.nov) {
-          val = win[rsr::kOverflowBase + lane];
-          par = reinterpret_cast<const uint16_t*>(slots + D.slot_off + D.nsl)[lane];
-        }
+      if (D.nov > 0) {
+        // further pieces of segments: their sums sit in overflow slots and count wherever the bits of
+        // the segment's value (the parent, listed in the first positions of the stream) say so
+        const uint32_t parw = (full > 0) ? e[0][0] : et[0];
 #pragma unroll
-        for (int beta = 0; beta < 7; ++beta) vals[beta] += ((par >> beta) & 1) ? val : (AT)0;
-        ov7 = lane63<AT>(wave_sum_to_lane63<AT>(((par >> 7) & 1) ? val : (AT)0));
-        ov8 = lane63<AT>(wave_sum_to_lane63<AT>(((par >> 8) & 1) ? val : (AT)0));
-        ovt = lane63<AT>(wave_sum_to_lane63<AT>(val));
+        for (int c = 0; c < rsr::kMaxOverflow / 64; ++c) {
+          if (c * 64 < D.nov) {
+            const AT val = win[rsr::kOverflowBase + c * 64 + lane];  // unused overflow slots hold 0
+            const uint32_t par = (c == 0) ? (parw & 0xffffu) : (parw >> 16);
+#pragma unroll
+            for (int beta = 0; beta < 7; ++beta) vals[beta] += ((par >> beta) & 1) ? val : (AT)0;
+            ov7 += wave_sum_to_lane63<AT>(((par >> 7) & 1) ? val : (AT)0);
+            ov8 += wave_sum_to_lane63<AT>(((par >> 8) & 1) ? val : (AT)0);
+            ovt += wave_sum_to_lane63<AT>(val);
+          }
+        }
+        ov7 = read_lane<AT>(ov7, 63); ov8 = read_lane<AT>(ov8, 63); ovt = read_lane<AT>(ovt, 63);
       }
       const AT rowsum = row_sums_of_eight<AT>(vals, lane);
       win[lane] = rowsum;  // the window has been read: its first 64 slots carry the four rows across
@@ -457,7 +488,7 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
       unsigned before = 0;
       if (lane < 8) {
         const AT r0 = win[lane], r1 = win[16 + lane], r2 = win[32 + lane], r3 = win[48 + lane];
-        AT* rr = rec + (size_t)(ui - u_begin) * rsr::kRecordWords;
+        AT* rr = rec + (size_t)ix * rsr::kRecordWords;
         rr[lane == 7 ? 9 : lane] = ((r0 + r1) + (r2 + r3)) + (lane == 7 ? ovt : (AT)0);
         if (lane == 7) {
           rr[7] = (r1 + r3) + ov7;  // lane bit 4 = rows 1 and 3 = value bit 7
@@ -472,7 +503,7 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
         // Lane (bit + 16 * part) adds up, over the block's units, "sum of u[j] over the values j
         // with bit `bit` set".  Bits below kw are in the unit records; a higher bit sees only
         // window totals (the remaining levels of the fold act on the windows' sums).
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the records were written by this workgroup: no wider scope
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the records were written by this workgroup
         const int bit = lane & 15, q = lane >> 4;
         const AT* rr = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
         const int word = (bit < p.kw) ? bit : 9;
@@ -490,17 +521,15 @@ rsr_matvec_kernel(const uint4* __restrict__ entries, const uint4* __restrict__ s
         const int col = p.k - 1 - bit;
         if (lane < 16 && bit < p.k && col < width) outp[(int64_t)D.block * p.k + col] = res;
       }
+      ix = ix1; D = D1;
+      ix1 = ix2; dw1 = dw2;
+    };
 
-      // ---- take the unit after next and fetch its descriptor ----
-      uint32_t ui_nn = u_end, dw_nn = 0;
-      if (have_next) {
-        unsigned take = 0;
-        if (lane == 0) take = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-        ui_nn = u_begin + (uint32_t)__builtin_amdgcn_readfirstlane(take);
-        if (ui_nn < u_end) dw_nn = unit_words[(size_t)ui_nn * 16 + (lane & 15)];
-      }
-      ui = ui_next; dw = dw_next; D = Dn;
-      ui_next = ui_nn; dw_next = dw_nn;
+    while (ix < n_tot) {
+      unit(eA, tA, eB, tB);
+      if (ix >= n_tot) break;
+      unit(eB, tB, eA, tA);
+      if (ix >= n_tot) break;
     }
     rb0 = rb1;
     __syncthreads();
@@ -565,33 +594,29 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
 
   auto kern = rsr_matvec_kernel<VT>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream),
-                     static_cast<const uint4*>(h->d_entries), static_cast<const uint4*>(h->d_slots),
-                     static_cast<const uint32_t*>(h->d_units), static_cast<const uint32_t*>(h->d_blk_unit), v,
+                     static_cast<const unsigned char*>(h->d_stream), static_cast<const uint32_t*>(h->d_units), static_cast<const uint32_t*>(h->d_blk_unit), v,
                      static_cast<typename Acc<VT>::type*>(out), p);
   RSR_HIP_TRY(hipGetLastError());
   return RSR_OK;
 }
 
 void free_tables(rsr_handle* h) {
-  if (h->d_entries) (void)hipFree(h->d_entries);
-  if (h->d_slots) (void)hipFree(h->d_slots);
+  if (h->d_stream) (void)hipFree(h->d_stream);
   if (h->d_units) (void)hipFree(h->d_units);
   if (h->d_blk_unit) (void)hipFree(h->d_blk_unit);
-  h->d_entries = h->d_slots = h->d_units = h->d_blk_unit = nullptr;
+  h->d_stream = h->d_units = h->d_blk_unit = nullptr;
 }
 
 int upload(rsr_handle* h, const rsr::Packed& P) {
-  h->entry_bytes = P.entries.size() * sizeof(uint16_t);
-  h->slot_bytes = P.slots.size() * sizeof(uint16_t);
+  h->stream_bytes = P.stream.size() * sizeof(uint16_t);
   h->unit_bytes = P.units.size() * sizeof(rsr::Unit);
   h->blk_bytes = P.blk_unit.size() * sizeof(uint32_t);
-  // 16 spare bytes keep every stream non-empty and 16-byte loads of a final granule in bounds
-  RSR_HIP_TRY(hipMalloc(&h->d_entries, h->entry_bytes + 16));
-  RSR_HIP_TRY(hipMalloc(&h->d_slots, h->slot_bytes + 16));
-  RSR_HIP_TRY(hipMalloc(&h->d_units, h->unit_bytes + 16));
+  // The first KB of the stream is what the loads a unit does not need read: it has to exist.
+  RSR_HIP_TRY(hipMalloc(&h->d_stream, h->stream_bytes + 1024));
+  RSR_HIP_TRY(hipMalloc(&h->d_units, h->unit_bytes + 32));
   RSR_HIP_TRY(hipMalloc(&h->d_blk_unit, h->blk_bytes + 16));
-  if (h->entry_bytes) RSR_HIP_TRY(hipMemcpy(h->d_entries, P.entries.data(), h->entry_bytes, hipMemcpyHostToDevice));
-  if (h->slot_bytes) RSR_HIP_TRY(hipMemcpy(h->d_slots, P.slots.data(), h->slot_bytes, hipMemcpyHostToDevice));
+  RSR_HIP_TRY(hipMemset(static_cast<unsigned char*>(h->d_stream) + h->stream_bytes, 0, 1024));
+  if (h->stream_bytes) RSR_HIP_TRY(hipMemcpy(h->d_stream, P.stream.data(), h->stream_bytes, hipMemcpyHostToDevice));
   if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(h->d_units, P.units.data(), h->unit_bytes, hipMemcpyHostToDevice));
   RSR_HIP_TRY(hipMemcpy(h->d_blk_unit, P.blk_unit.data(), h->blk_bytes, hipMemcpyHostToDevice));
   RSR_HIP_TRY(hipDeviceSynchronize());
@@ -628,6 +653,7 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   h->k = P.k; h->kw = P.kw; h->parts = P.parts; h->last_width = P.last_width;
   h->max_units_per_block = P.max_units_per_block;
   h->stored_rows = P.stored_rows; h->segments = P.segments; h->nunits = (int64_t)P.units.size();
+  h->header_positions = P.header_positions;
   h->waves = env_int("RSR_WAVES", 16);
   if (h->waves < 1) h->waves = 1;
   if (h->waves > 16) h->waves = 16;
@@ -667,8 +693,8 @@ int rsr_info(const rsr_handle* h, rsr_info_t* info) {
   info->nblocks = h->nblocks; info->last_block_width = h->last_width;
   info->lo_bits = h->kw; info->hi_bits = h->k - h->kw;
   info->stored_rows = h->stored_rows; info->segments = h->segments; info->work_units = h->nunits;
-  info->index_bytes = (int64_t)h->entry_bytes;
-  info->segment_bytes = (int64_t)h->slot_bytes;
+  info->segment_bytes = h->header_positions * rsr::kPositionBytes;
+  info->index_bytes = (int64_t)h->stream_bytes - info->segment_bytes;
   info->schedule_bytes = (int64_t)(h->unit_bytes + h->blk_bytes);
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
   info->device = h->device; info->compute_units = h->num_cu;
@@ -681,8 +707,7 @@ int rsr_export_block(rsr_handle* h, int part, int64_t block, int32_t* sigma, int
     std::unique_ptr<rsr::Packed> P(new (std::nothrow) rsr::Packed());
     if (!P) return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
     try {
-      P->entries.resize(h->entry_bytes / sizeof(uint16_t));
-      P->slots.resize(h->slot_bytes / sizeof(uint16_t));
+      P->stream.resize(h->stream_bytes / sizeof(uint16_t));
       P->units.resize(h->unit_bytes / sizeof(rsr::Unit));
       P->blk_unit.resize(h->blk_bytes / sizeof(uint32_t));
     } catch (const std::bad_alloc&) {
@@ -693,8 +718,7 @@ int rsr_export_block(rsr_handle* h, int part, int64_t block, int32_t* sigma, int
     int dev = 0;
     RSR_HIP_TRY(hipGetDevice(&dev));
     RSR_HIP_TRY(hipSetDevice(h->device));
-    if (h->entry_bytes) RSR_HIP_TRY(hipMemcpy(P->entries.data(), h->d_entries, h->entry_bytes, hipMemcpyDeviceToHost));
-    if (h->slot_bytes) RSR_HIP_TRY(hipMemcpy(P->slots.data(), h->d_slots, h->slot_bytes, hipMemcpyDeviceToHost));
+    if (h->stream_bytes) RSR_HIP_TRY(hipMemcpy(P->stream.data(), h->d_stream, h->stream_bytes, hipMemcpyDeviceToHost));
     if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(P->units.data(), h->d_units, h->unit_bytes, hipMemcpyDeviceToHost));
     RSR_HIP_TRY(hipMemcpy(P->blk_unit.data(), h->d_blk_unit, h->blk_bytes, hipMemcpyDeviceToHost));
     RSR_HIP_TRY(hipSetDevice(dev));
@@ -743,13 +767,11 @@ int rsr_host_export_block(const rsr_host_index* x, int part, int64_t block, int3
   return RSR_OK;
 }
 
-int rsr_host_streams(const rsr_host_index* x, const uint16_t** entries, int64_t* n_entries, const uint16_t** slots,
-                     int64_t* n_slots, const void** units, int64_t* n_units, const uint32_t** blk_unit) {
+int rsr_host_streams(const rsr_host_index* x, const uint16_t** stream, int64_t* n_stream, const void** units,
+                     int64_t* n_units, const uint32_t** blk_unit) {
   if (!valid(x)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index");
-  if (entries) *entries = x->P.entries.data();
-  if (n_entries) *n_entries = (int64_t)x->P.entries.size();
-  if (slots) *slots = x->P.slots.data();
-  if (n_slots) *n_slots = (int64_t)x->P.slots.size();
+  if (stream) *stream = x->P.stream.data();
+  if (n_stream) *n_stream = (int64_t)x->P.stream.size();
   if (units) *units = x->P.units.data();
   if (n_units) *n_units = (int64_t)x->P.units.size();
   if (blk_unit) *blk_unit = x->P.blk_unit.data();

@@ -11,75 +11,97 @@ namespace {
 
 struct Piece {
   uint32_t start;   // first sorted position of the piece inside the block's permutation
-  uint16_t len;     // rows in the piece, 1 .. kMaxDiag
+  uint16_t len;     // rows, 1 .. kMaxPieceRows
   uint16_t slot;    // value of the segment inside its window (0 .. 2^kw - 1)
 };
 
 struct BlockOut {
-  std::vector<uint16_t> entries, slots;
+  std::vector<uint16_t> stream;
   std::vector<Unit> units;
-  int64_t stored_rows = 0, segments = 0;
+  int64_t stored_rows = 0, segments = 0, header_positions = 0;
 };
+
+// Longest piece: its group (header + rows) and two parent positions have to fit into one unit.
+constexpr int kMaxPieceRows = kMaxPositions - 3;
+// Cost of a work unit beyond its positions (descriptor, window clearing, fold), in positions.
+constexpr int kUnitCost = 3;
 
 struct Scratch {
   std::vector<uint16_t> val[2];     // value of every row, per part
   std::vector<uint32_t> off;        // 2^k + 1 exclusive prefix counts (the full segmentation)
   std::vector<uint32_t> pos;
   std::vector<uint16_t> sigma;      // sorted rows (Definition 3.2, equal rows in ascending order)
-  std::vector<Piece> pieces, sorted, leftover, unit_pieces;
-  std::vector<uint16_t> unit_slot, parents;
+  std::vector<Piece> pieces, sorted;
+  std::vector<uint16_t> unit_slot, parents, positions;
   std::vector<uint8_t> seen;
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// One unit: up to 512 pieces (already sorted by descending length) of one window.
-void emit_unit(const std::vector<Piece>& pcs, const std::vector<uint16_t>& slot_ids,
-               const std::vector<uint16_t>& parents, const std::vector<uint16_t>& sigma, uint32_t block,
-               uint32_t window, int part, uint16_t null_index, BlockOut* out) {
+// One unit: pcs[first .. first+count) (sorted by descending length, count a multiple of 64 except
+// in the last unit of a window), their slots, and the parents of the overflow slots among them.
+void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std::vector<uint16_t>& parents,
+               const std::vector<uint16_t>& sigma, uint32_t block, uint32_t window, int part, uint16_t null_index,
+               std::vector<uint16_t>& positions, BlockOut* out) {
+  positions.clear();
+  int npos = 0;
+  auto add_position = [&](uint16_t fill) {
+    positions.resize((size_t)(npos + 1) * kLanes, fill);
+    return &positions[(size_t)npos++ * kLanes];
+  };
+  const int nov = (int)parents.size();
+  for (int c = 0; c * kLanes < nov; ++c) {
+    uint16_t* q = add_position(null_index);
+    for (int l = 0; l < kLanes && c * kLanes + l < nov; ++l) q[l] = parents[(size_t)c * kLanes + l];
+  }
+  uint64_t hdr = 0;
+  int ngroups = 0;
+  uint32_t nidx = 0;
+  for (int r0 = 0; r0 < count; r0 += kLanes) {
+    const int n = pcs[r0].len;  // the group's longest piece
+    const int cnt = std::min(kLanes, count - r0);
+    hdr |= 1ull << npos;
+    uint16_t* h = add_position(0);
+    for (int l = 0; l < kLanes; ++l) h[l] = (l < cnt) ? slot_ids[r0 + l] : (uint16_t)(kWindow + (l & (kDummySlots - 1)));
+    for (int t = 0; t < n; ++t) {
+      uint16_t* e = add_position(null_index);
+      for (int l = 0; l < cnt; ++l)
+        if (t < pcs[r0 + l].len) { e[l] = sigma[pcs[r0 + l].start + t]; ++nidx; }
+    }
+    ++ngroups;
+  }
+  if (npos & 1) add_position(null_index);  // dword rows hold two positions
   Unit u;
   std::memset(&u, 0, sizeof(u));
-  const int np = (int)pcs.size();
-  const int nt = np ? pcs[0].len : 0;
-  u.entry_off = (uint32_t)(out->entries.size() / kPerLane);
-  u.slot_off = (uint32_t)(out->slots.size() / kPerLane);
+  u.stream_off = (uint32_t)(out->stream.size() * sizeof(uint16_t) / kStreamAlign);
   u.block = block;
   u.window = (uint16_t)window;
-  u.npieces = (uint16_t)np;
-  u.nt = (uint8_t)nt;
   u.part = (uint8_t)part;
-  u.nov = (uint8_t)parents.size();
-  int cnt = np;
-  int nt_main = nt;
-  int granules = 0;
-  for (int t = 0; t < nt; ++t) {
-    while (cnt > 0 && pcs[cnt - 1].len <= t) --cnt;
-    if (nt_main == nt && cnt <= kTailRanks) nt_main = t;  // from here on one entry per lane suffices
-    if (t < nt_main) {
-      const int c8 = ceil_div(cnt, kPerLane);
-      u.cnt8[t] = (uint8_t)c8;
-      granules += c8;
-      for (int q = 0; q < c8 * kPerLane; ++q)
-        out->entries.push_back(q < cnt ? sigma[pcs[q].start + t] : null_index);
-    } else {
-      u.cnt8[t] = (uint8_t)cnt;
-      for (int q = 0; q < cnt; ++q) out->entries.push_back(sigma[pcs[q].start + t]);
+  u.nov = (uint8_t)nov;
+  u.npos = (uint8_t)npos;
+  u.ngroups = (uint8_t)ngroups;
+  u.hdr_lo = (uint32_t)hdr;
+  u.hdr_hi = (uint32_t)(hdr >> 32);
+  u.nidx = nidx;
+  u.npieces = (uint32_t)count;
+  const int full = npos / kGranulePositions;
+  for (int g = 0; g < full; ++g)
+    for (int l = 0; l < kLanes; ++l)
+      for (int q = 0; q < kGranulePositions; ++q)
+        out->stream.push_back(positions[(size_t)(g * kGranulePositions + q) * kLanes + l]);
+  for (int p = full * kGranulePositions; p < npos; p += 2)
+    for (int l = 0; l < kLanes; ++l) {
+      out->stream.push_back(positions[(size_t)p * kLanes + l]);
+      out->stream.push_back(positions[(size_t)(p + 1) * kLanes + l]);
     }
-    out->stored_rows += cnt;
-  }
-  while (out->entries.size() % kPerLane) out->entries.push_back(null_index);
-  u.nt_main = (uint8_t)nt_main;
-  u.main_granules = (uint16_t)granules;
-  const int ns = ceil_div(np, kPerLane) * kPerLane;
-  for (int q = 0; q < ns; ++q) out->slots.push_back(q < np ? slot_ids[q] : (uint16_t)kWindow);
-  const int nov = (int)parents.size();
-  const int npar = ceil_div(nov, kPerLane) * kPerLane;
-  for (int o = 0; o < npar; ++o) out->slots.push_back(o < nov ? parents[o] : (uint16_t)0);
-  out->segments += np;
+  out->stored_rows += nidx;
+  out->segments += count;
+  out->header_positions += ngroups;
   out->units.push_back(u);
 }
 
-// All windows of one (block, part): cut segments into pieces, rank by length, emit units.
+// All windows of one (block, part): sort the rows, cut each window's segments into pieces of at
+// most T rows, rank the pieces by length, fill units group by group.
 void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S, BlockOut* out) {
   const uint32_t nvals = 1u << k;
   const uint32_t W = 1u << kw;
@@ -96,57 +118,103 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
   const uint32_t nwin = nvals >> kw;
   for (uint32_t w = 0; w < nwin; ++w) {
     const uint32_t j0 = w * W;
-    if (S->off[j0 + W] == S->off[j0 + (w == 0 ? 1 : 0)]) continue;  // nothing but value 0 here
+    const uint32_t jfirst = (w == 0 ? 1 : 0);  // value 0 contributes nothing
+    if (S->off[j0 + W] == S->off[j0 + jfirst]) continue;
+    // ---- the cut length T: the one with the fewest positions (plus a charge per unit) ----
+    uint32_t longest = 0;
+    for (uint32_t jl = jfirst; jl < W; ++jl) longest = std::max(longest, S->off[j0 + jl + 1] - S->off[j0 + jl]);
+    int best_T = 1, best_cost = 0x7fffffff;
+    for (int T = std::min<uint32_t>(longest, kMaxPieceRows); T >= 1; --T) {
+      uint32_t hist[kMaxPieceRows + 1] = {0};
+      uint32_t nov = 0;
+      for (uint32_t jl = jfirst; jl < W; ++jl) {
+        const uint32_t c = S->off[j0 + jl + 1] - S->off[j0 + jl];
+        if (!c) continue;
+        hist[T] += c / (uint32_t)T;
+        if (c % (uint32_t)T) ++hist[c % (uint32_t)T];
+        nov += (c + (uint32_t)T - 1) / (uint32_t)T - 1;
+      }
+      // groups of 64 in descending length: a group costs its header and its longest piece
+      int cost = 0;
+      uint32_t in_group = 0;
+      for (int len = T; len >= 1; --len) {
+        uint32_t n = hist[len];
+        while (n) {
+          if (in_group == 0) cost += 1 + len;
+          const uint32_t take = std::min<uint32_t>(n, kLanes - in_group);
+          in_group = (in_group + take) % kLanes;
+          n -= take;
+        }
+      }
+      cost += ceil_div((int)nov, kLanes);
+      const int units = std::max(ceil_div(cost, kMaxPositions - 2), ceil_div((int)nov, kMaxOverflow));
+      cost += units * kUnitCost;
+      if (cost < best_cost) { best_cost = cost; best_T = T; }
+      if (nov > (uint32_t)8 * kMaxOverflow && cost > 2 * best_cost) break;  // shorter pieces only get worse
+    }
+    // ---- pieces, ranked by descending length (stable counting sort) ----
+    const uint32_t T = (uint32_t)best_T;
     S->pieces.clear();
-    for (uint32_t jl = (w == 0 ? 1 : 0); jl < W; ++jl) {  // value 0 contributes nothing
+    for (uint32_t jl = jfirst; jl < W; ++jl) {
       const uint32_t j = j0 + jl;
       const uint32_t c = S->off[j + 1] - S->off[j];
-      if (c == 0) continue;
-      if (c <= (uint32_t)kMaxDiag) {
-        S->pieces.push_back(Piece{S->off[j], (uint16_t)c, (uint16_t)jl});
-      } else {
-        const uint32_t m = (c + kMaxDiag - 1) / kMaxDiag, base = c / m, rem = c % m;
-        uint32_t s = S->off[j];
-        for (uint32_t i = 0; i < m; ++i) {
-          const uint32_t len = base + (i < rem ? 1 : 0);
-          S->pieces.push_back(Piece{s, (uint16_t)len, (uint16_t)jl});
-          s += len;
-        }
-      }
+      for (uint32_t done = 0; done < c; done += T)
+        S->pieces.push_back(Piece{S->off[j] + done, (uint16_t)std::min(T, c - done), (uint16_t)jl});
     }
-    // stable counting sort by descending length
-    uint32_t bucket[kMaxDiag + 2] = {0};
-    for (const Piece& p : S->pieces) ++bucket[kMaxDiag - p.len + 1];
-    for (int i = 0; i <= kMaxDiag; ++i) bucket[i + 1] += bucket[i];
+    uint32_t bucket[kMaxPieceRows + 2] = {0};
+    for (const Piece& p : S->pieces) ++bucket[kMaxPieceRows - p.len + 1];
+    for (int i = 0; i <= kMaxPieceRows; ++i) bucket[i + 1] += bucket[i];
     S->sorted.resize(S->pieces.size());
-    for (const Piece& p : S->pieces) S->sorted[bucket[kMaxDiag - p.len]++] = p;
+    for (const Piece& p : S->pieces) S->sorted[bucket[kMaxPieceRows - p.len]++] = p;
 
-    // fill units; a second piece of a value inside one unit takes an overflow slot
-    std::vector<Piece>* cur = &S->sorted;
-    while (!cur->empty()) {
-      S->unit_pieces.clear();
-      S->unit_slot.clear();
+    // ---- units: consecutive groups while positions and overflow slots last ----
+    const int np = (int)S->sorted.size();
+    S->unit_slot.resize((size_t)np);
+    int first = 0;        // first piece of the unit being filled
+    int posn = 0;         // its positions without the parent positions
+    S->parents.clear();
+    S->seen.assign(W, 0);
+    auto flush_unit = [&](int end) {
+      emit_unit(&S->sorted[(size_t)first], &S->unit_slot[(size_t)first], end - first, S->parents, S->sigma, block, w, part,
+                null_index, S->positions, out);
+      first = end;
+      posn = 0;
       S->parents.clear();
-      S->leftover.clear();
       S->seen.assign(W, 0);
-      for (const Piece& p : *cur) {
-        if ((int)S->unit_pieces.size() >= kTileRanks) { S->leftover.push_back(p); continue; }
-        if (!S->seen[p.slot]) {
-          S->seen[p.slot] = 1;
-          S->unit_pieces.push_back(p);
-          S->unit_slot.push_back(p.slot);
-        } else if ((int)S->parents.size() < kMaxOverflow) {
-          S->unit_pieces.push_back(p);
-          S->unit_slot.push_back((uint16_t)(kOverflowBase + S->parents.size()));
-          S->parents.push_back(p.slot);
-        } else {
-          S->leftover.push_back(p);
+    };
+    for (int r0 = 0; r0 < np; r0 += kLanes) {
+      const int cnt = std::min(kLanes, np - r0);
+      const int need = 1 + (int)S->sorted[(size_t)r0].len;
+      for (int attempt = 0;; ++attempt) {
+        int extra = 0;  // pieces of this group whose segment already has a piece in the unit (or in this group)
+        for (int l = 0; l < cnt; ++l) {
+          const uint16_t sl = S->sorted[(size_t)(r0 + l)].slot;
+          if (S->seen[sl]) ++extra; else S->seen[sl] = 2;  // 2: tentatively, by this group
         }
+        const int nov = (int)S->parents.size() + extra;
+        const bool fits = nov <= kMaxOverflow && posn + need + ceil_div(nov, kLanes) <= kMaxPositions;
+        if (fits || attempt == 1) {
+          for (int l = 0; l < cnt; ++l) {
+            Piece& pc = S->sorted[(size_t)(r0 + l)];
+            if (S->seen[pc.slot] == 2) {
+              S->seen[pc.slot] = 1;
+              S->unit_slot[(size_t)(r0 + l)] = pc.slot;
+            } else {
+              S->unit_slot[(size_t)(r0 + l)] = (uint16_t)(kOverflowBase + S->parents.size());
+              S->parents.push_back(pc.slot);
+            }
+          }
+          posn += need;
+          break;
+        }
+        for (int l = 0; l < cnt; ++l) {  // undo the tentative marks, close the unit, try again in an empty one
+          uint8_t& m = S->seen[S->sorted[(size_t)(r0 + l)].slot];
+          if (m == 2) m = 0;
+        }
+        flush_unit(r0);
       }
-      emit_unit(S->unit_pieces, S->unit_slot, S->parents, S->sigma, block, w, part, null_index, out);
-      S->sorted.swap(S->leftover);  // leftover keeps the descending order
-      cur = &S->sorted;
     }
+    if (first < np) flush_unit(np);
   }
 }
 
@@ -181,10 +249,9 @@ void extract_values(const int8_t* A, int64_t rows, int64_t cols, int k, int part
 
 void pack_block(int64_t rows, int k, int kw, int parts, int64_t block, Scratch* S, BlockOut* out) {
   for (int p = 0; p < parts; ++p) pack_part(rows, k, kw, (uint32_t)block, p, S, out);
-  if (out->units.empty()) {  // an all-zero block still has to write its outputs
-    const std::vector<Piece> none;
-    const std::vector<uint16_t> no_ids;
-    emit_unit(none, no_ids, no_ids, S->sigma, (uint32_t)block, 0, 0, (uint16_t)rows, out);
+  if (out->units.empty()) {  // an all-zero block still has to write its outputs: a unit without positions
+    S->parents.clear();
+    emit_unit(nullptr, nullptr, 0, S->parents, S->sigma, (uint32_t)block, 0, 0, (uint16_t)rows, S->positions, out);
   }
 }
 
@@ -270,35 +337,42 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
   P = Packed();
   P.rows = rows; P.cols = cols; P.k = k; P.kw = kw; P.parts = parts; P.nblocks = nblocks;
   P.last_width = (int)(cols - (nblocks - 1) * k);
-  size_t ne = 0, ns = 0, nu = 0;
-  for (const BlockOut& b : blocks) { ne += b.entries.size(); ns += b.slots.size(); nu += b.units.size(); }
-  if (ne / kPerLane > 0xffffffffull || nu > 0xffffffffull) { *err = "index too large"; return -2; }
+  size_t ne = 0, nu = 0;
+  for (const BlockOut& b : blocks) { ne += b.stream.size(); nu += b.units.size(); }
+  if (ne * sizeof(uint16_t) / kStreamAlign > 0xffffffffull || nu > 0xffffffffull) { *err = "index too large"; return -2; }
   try {
-    P.entries.resize(ne); P.slots.resize(ns); P.units.resize(nu); P.blk_unit.resize((size_t)nblocks + 1);
+    P.stream.resize(ne); P.units.resize(nu); P.blk_unit.resize((size_t)nblocks + 1);
   } catch (...) { *err = "out of host memory while packing"; return -4; }
-  size_t pe = 0, ps = 0, pu = 0;
+  size_t pe = 0, pu = 0;
   for (int64_t b = 0; b < nblocks; ++b) {
     BlockOut& B = blocks[(size_t)b];
     P.blk_unit[(size_t)b] = (uint32_t)pu;
-    if (!B.entries.empty()) std::memcpy(&P.entries[pe], B.entries.data(), B.entries.size() * sizeof(uint16_t));
-    if (!B.slots.empty()) std::memcpy(&P.slots[ps], B.slots.data(), B.slots.size() * sizeof(uint16_t));
+    if (!B.stream.empty()) std::memcpy(&P.stream[pe], B.stream.data(), B.stream.size() * sizeof(uint16_t));
+    if (B.units.size() > 0xffffu) { *err = "too many work units in one column block"; return -2; }
     for (size_t i = 0; i < B.units.size(); ++i) {
       Unit u = B.units[i];
-      u.entry_off += (uint32_t)(pe / kPerLane);
-      u.slot_off += (uint32_t)(ps / kPerLane);
+      u.stream_off += (uint32_t)(pe * sizeof(uint16_t) / kStreamAlign);
       u.units_in_block = (uint16_t)B.units.size();
       P.units[pu + i] = u;
     }
-    if (B.units.size() > 0xffffu) { *err = "too many work units in one column block"; return -2; }
     P.max_units_per_block = std::max<uint32_t>(P.max_units_per_block, (uint32_t)B.units.size());
     P.stored_rows += B.stored_rows;
     P.segments += B.segments;
-    pe += B.entries.size(); ps += B.slots.size(); pu += B.units.size();
-    BlockOut().entries.swap(B.entries);
-    BlockOut().slots.swap(B.slots);
+    P.header_positions += B.header_positions;
+    pe += B.stream.size(); pu += B.units.size();
+    std::vector<uint16_t>().swap(B.stream);
   }
   P.blk_unit[(size_t)nblocks] = (uint32_t)pu;
   return 0;
+}
+
+// Position p, lane l of a unit's stream.
+static inline uint16_t stream_at(const uint16_t* us, int npos, int p, int l) {
+  const int full = npos / kGranulePositions;
+  if (p < full * kGranulePositions)
+    return us[((size_t)(p / kGranulePositions) * kLanes + l) * kGranulePositions + p % kGranulePositions];
+  const int q = p - full * kGranulePositions;
+  return us[(size_t)full * kGranulePositions * kLanes + ((size_t)(q / 2) * kLanes + l) * 2 + (q & 1)];
 }
 
 int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32_t* L, std::string* err) {
@@ -313,28 +387,34 @@ int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32
   for (uint32_t ui = P.blk_unit[(size_t)block]; ui < P.blk_unit[(size_t)block + 1]; ++ui) {
     const Unit& u = P.units[ui];
     if (u.part != part) continue;
-    const uint16_t* e = &P.entries[(size_t)u.entry_off * kPerLane];
-    const uint16_t* s = &P.slots[(size_t)u.slot_off * kPerLane];
-    const int ns = ceil_div(u.npieces, kPerLane) * kPerLane;
-    for (int t = 0; t < u.nt; ++t) {
-      const int n = (t < u.nt_main) ? u.cnt8[t] * kPerLane : u.cnt8[t];
-      for (int q = 0; q < n; ++q) {
-        const uint16_t row = e[q];
+    if (u.npos > kMaxPositions || (u.npos & 1)) { *err = "corrupt unit: position count"; return -1; }
+    const uint16_t* us = &P.stream[(size_t)u.stream_off * (kStreamAlign / sizeof(uint16_t))];
+    const uint64_t hdr = ((uint64_t)u.hdr_hi << 32) | u.hdr_lo;
+    const int npar = (u.nov + kLanes - 1) / kLanes;
+    if (u.nov > kMaxOverflow || npar > u.npos) { *err = "corrupt unit: overflow slots"; return -1; }
+    uint16_t slot[kLanes];
+    for (int l = 0; l < kLanes; ++l) slot[l] = (uint16_t)kWindow;
+    for (int p = npar; p < u.npos; ++p) {
+      if ((hdr >> p) & 1) {
+        for (int l = 0; l < kLanes; ++l) slot[l] = stream_at(us, u.npos, p, l);
+        continue;
+      }
+      for (int l = 0; l < kLanes; ++l) {
+        const uint16_t row = stream_at(us, u.npos, p, l);
         if (row == null_index) continue;
-        if (q >= u.npieces || row > null_index) { *err = "corrupt unit: entry beyond its pieces"; return -1; }
-        uint32_t slot = s[q];
-        if (slot >= (uint32_t)kOverflowBase) {
-          const uint32_t o = slot - kOverflowBase;
+        if (row > null_index) { *err = "corrupt unit: row index out of range"; return -1; }
+        uint32_t sl = slot[l];
+        if (sl >= (uint32_t)kOverflowBase) {  // a further piece of a segment: filed under its parent
+          const uint32_t o = sl - kOverflowBase;
           if (o >= u.nov) { *err = "corrupt unit: overflow slot out of range"; return -1; }
-          slot = s[ns + o];
+          sl = stream_at(us, u.npos, (int)(o / kLanes), (int)(o % kLanes));
         }
-        if (slot >= (uint32_t)kWindow) { *err = "corrupt unit: row in a dummy slot"; return -1; }
-        const uint32_t value = (((uint32_t)u.window << P.kw) + slot) >> shift;
+        if (sl >= (uint32_t)kWindow) { *err = "corrupt unit: row in a dummy slot"; return -1; }
+        const uint32_t value = (((uint32_t)u.window << P.kw) + sl) >> shift;
         if (value >= nvals || value == 0 || listed[row]) { *err = "corrupt unit: bad value or repeated row"; return -1; }
         listed[row] = 1;
         by_value[value].push_back((int32_t)row);
       }
-      e += n;
     }
   }
   for (int64_t r = 0; r < P.rows; ++r)

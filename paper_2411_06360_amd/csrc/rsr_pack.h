@@ -16,12 +16,12 @@ struct Packed {
   int64_t rows = 0, cols = 0;
   int k = 0, kw = 0, parts = 0, last_width = 0;
   int64_t nblocks = 0;
-  std::vector<uint16_t> entries;   // multiple of 8 elements per unit diagonal
-  std::vector<uint16_t> slots;     // slot ids and overflow parents, multiples of 8 elements
+  std::vector<uint16_t> stream;    // unit streams (headers and row indices), 128 elements per position pair
   std::vector<Unit> units;
   std::vector<uint32_t> blk_unit;  // nblocks + 1
-  int64_t stored_rows = 0;         // real (non-null) row indices in `entries`
+  int64_t stored_rows = 0;         // real (non-null) row indices in `stream`
   int64_t segments = 0;            // pieces
+  int64_t header_positions = 0;    // positions that hold slot ids rather than row indices
   uint32_t max_units_per_block = 0;
 };
 

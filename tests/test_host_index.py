@@ -18,7 +18,7 @@ from oracle import dense, steps
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 # layout constants of csrc/rsr_format.h
-WINDOW, DUMMY, OVF_BASE, MAX_OVF, WIN_SLOTS, TILE, MAX_DIAG = 512, 8, 520, 64, 584, 512, 40
+WINDOW, DUMMY, OVF_BASE, MAX_OVF, WIN_SLOTS, LANES, MAX_POS, ALIGN = 512, 8, 520, 128, 648, 64, 48, 256
 
 
 def rng(seed):
@@ -112,7 +112,7 @@ CASES = [
     (700, 26, 13, "ternary", 5),    # ragged last block of width 13 -> exactly 2 blocks
     (100, 33, 16, "ternary", 6),    # widest k, ragged last block of width 1
     (40, 7, 1, "ternary", 7),
-    (2000, 20, 5, "binary", 8),     # long segments (about 62 rows): overflow pieces
+    (2000, 20, 5, "binary", 8),     # long segments (about 62 rows): several pieces each
 ]
 
 
@@ -148,75 +148,99 @@ def test_ternary_without_minus_ones_is_binary_and_negative_only_is_ternary():
 
 
 # ---- the packed streams: what the kernels rely on ----------------------------------------------------
+def unit_positions(stream, U):
+    """The unit's stream as an array [position][lane], undoing the granule order of the device."""
+    npos = int(U["npos"])
+    base = int(U["stream_off"]) * (ALIGN // 2)
+    full = npos // 8
+    pos = np.empty((npos, LANES), dtype=np.int64)
+    if full:
+        g = stream[base : base + full * 8 * LANES].reshape(full, LANES, 8)
+        pos[: full * 8] = g.transpose(0, 2, 1).reshape(full * 8, LANES)
+    rest = npos - full * 8
+    if rest:
+        t = stream[base + full * 8 * LANES : base + npos * LANES].reshape(rest // 2, LANES, 2)
+        pos[full * 8 :] = t.transpose(0, 2, 1).reshape(rest, LANES)
+    return pos
+
+
+def unit_groups(U, pos):
+    """(parent positions, [(header position, index positions)]) of the unit."""
+    hdr = (int(U["hdr_hi"]) << 32) | int(U["hdr_lo"])
+    npar = -(-int(U["nov"]) // LANES)
+    heads = [p for p in range(int(U["npos"])) if (hdr >> p) & 1]
+    assert hdr >> int(U["npos"]) == 0 and len(heads) == int(U["ngroups"])
+    if heads:
+        assert heads[0] == npar  # the parents come first, then the first group
+    else:
+        assert npar == 0
+    return npar, [(h, list(range(h + 1, nxt))) for h, nxt in zip(heads, heads[1:] + [int(U["npos"])])]
+
+
 def check_streams(h, S):
     info = h.info
     rows, k, kw = info.rows, info.k, info.lo_bits
-    units, entries, slots, blk = S["units"], S["entries"], S["slots"], S["blk_unit"]
+    units, stream, blk = S["units"], S["stream"], S["blk_unit"]
     assert kw == min(k, 9)
-    assert len(entries) % 8 == 0 and len(slots) % 8 == 0
+    assert len(stream) % (ALIGN // 2) == 0
     assert len(blk) == info.nblocks + 1 and blk[0] == 0 and blk[-1] == len(units)
     assert np.all(np.diff(blk.astype(np.int64)) >= 1)  # every block has a unit: its outputs get written
-    assert info.index_bytes == 2 * len(entries) and info.segment_bytes == 2 * len(slots)
+    assert info.index_bytes + info.segment_bytes == 2 * len(stream)
+    assert info.segment_bytes == 128 * int(units["ngroups"].astype(np.int64).sum())
     assert info.work_units == len(units)
-    stored = 0
+    assert info.schedule_bytes == 32 * len(units) + 4 * len(blk)
+    stored = pieces = 0
+    next_off = 0
     for b in range(info.nblocks):
         seen = [set(), set()]
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
             assert U["block"] == b and U["part"] < info.parts
             assert U["units_in_block"] == blk[b + 1] - blk[b]
-            assert U["npieces"] <= TILE and U["nt"] <= MAX_DIAG and U["nov"] <= MAX_OVF
             assert U["window"] < (1 << (k - kw))
-            cnt8 = U["cnt8"].astype(int)
-            nt, ntm = int(U["nt"]), int(U["nt_main"])
-            assert ntm <= nt and np.all(cnt8[nt:] == 0)
-            per_diag = np.where(np.arange(40) < ntm, 8 * cnt8, cnt8)[:nt]  # stored entries per diagonal
-            assert np.all(np.diff(cnt8[:ntm]) <= 0) and np.all(np.diff(cnt8[ntm:nt]) <= 0)  # only ever shrink
-            assert np.all(cnt8[ntm:nt] <= 64) and np.all(cnt8[ntm:nt] >= 1)  # a tail diagonal: one entry per lane
-            assert np.all(cnt8[:ntm] * 8 > 64)  # ... and it starts as soon as 64 lanes suffice
-            assert int(U["main_granules"]) == int(cnt8[:ntm].sum())
-            nsl = -(-int(U["npieces"]) // 8)
-            if ntm:
-                assert cnt8[0] == nsl
-            off = int(U["entry_off"]) * 8
-            n_e = int(per_diag.sum())
-            n_e8 = -(-n_e // 8) * 8
-            assert off + n_e8 <= len(entries)
-            assert np.all(entries[off + n_e : off + n_e8] == rows)  # the tail region is padded with nulls
-            e = entries[off : off + n_e].astype(int)
-            assert np.all(e <= rows)  # row index or the null index
-            real = e[e < rows]
-            assert len(set(real.tolist())) == len(real) and not (set(real.tolist()) & seen[U["part"]])
-            seen[U["part"]] |= set(real.tolist())
-            stored += len(real)
-            so = int(U["slot_off"]) * 8
-            ids = slots[so : so + 8 * nsl].astype(int)
-            used = ids[: int(U["npieces"])]
-            assert np.all(ids[int(U["npieces"]) :] == WINDOW)  # padding ranks -> dummy slot
-            assert len(set(used.tolist())) == len(used)  # plain stores: one writer per slot
-            regular = used[used < WINDOW]
-            ovf = used[used >= WINDOW]
-            assert np.all(regular < (1 << kw))
-            assert sorted(ovf.tolist()) == list(range(OVF_BASE, OVF_BASE + int(U["nov"])))
-            npar = 8 * (-(-int(U["nov"]) // 8))
-            assert so + 8 * nsl + npar <= len(slots)
-            parents = slots[so + 8 * nsl : so + 8 * nsl + int(U["nov"])].astype(int)
-            assert set(parents.tolist()) <= set(regular.tolist())  # a cut segment keeps its first piece in place
-            # padding is null and sits only at the end of a wide diagonal; tail diagonals have none
-            p = off
-            lens = np.zeros(max(8 * nsl, 64), dtype=int)
-            for t in range(nt):
-                d = entries[p : p + per_diag[t]].astype(int)
-                valid = d < rows
-                nvalid = int(valid.sum())
-                assert np.all(valid[:nvalid]) and np.all(d[nvalid:] == rows)
-                if t >= ntm:
-                    assert nvalid == per_diag[t]
-                lens[:nvalid] += 1
-                p += per_diag[t]
-            assert np.all(np.diff(lens[: int(U["npieces"])]) <= 0)  # ranks are ordered by descending length
-            assert np.all(lens[: int(U["npieces"])] >= 1) or int(U["npieces"]) == 0
-    assert stored == info.stored_rows
+            npos, nov = int(U["npos"]), int(U["nov"])
+            assert npos % 2 == 0 and npos <= MAX_POS and nov <= MAX_OVF
+            assert int(U["stream_off"]) == next_off  # unit streams are back to back, 256-byte aligned
+            next_off += npos * LANES * 2 // ALIGN
+            pos = unit_positions(stream, U)
+            npar, groups = unit_groups(U, pos)
+            parents = pos[:npar].reshape(-1)
+            assert np.all(parents[:nov] < (1 << kw)) and np.all(parents[nov:] == rows)
+            used_slots = []
+            nidx = 0
+            last_len = None
+            for head, idxs in groups:
+                slots = pos[head]
+                assert np.all(slots < WIN_SLOTS)
+                body = pos[idxs] if idxs else np.empty((0, LANES), dtype=np.int64)
+                assert np.all(body <= rows)  # row index or the null index
+                real = body < rows
+                lens = real.sum(axis=0)
+                # a piece occupies the first positions of its lane; pieces are ranked by descending length
+                assert np.all(real == (np.arange(len(idxs))[:, None] < lens[None, :]))
+                assert np.all(np.diff(lens) <= 0) and (last_len is None or lens[0] <= last_len)
+                owners = lens > 0
+                last_len = lens[owners][-1] if owners.any() else last_len
+                assert np.all(slots[~owners] >= WINDOW) and np.all(slots[~owners] < OVF_BASE)  # dummies
+                own = slots[owners]
+                assert np.all((own < (1 << kw)) | ((own >= OVF_BASE) & (own < OVF_BASE + nov)))
+                # only the unit's last group may carry one all-null position (even position count)
+                assert lens[0] >= len(idxs) - (1 if head == groups[-1][0] else 0) and lens[0] >= 1
+                used_slots += own.tolist()
+                pieces += int(owners.sum())
+                rr = body[real].tolist()
+                assert len(set(rr)) == len(rr) and not (set(rr) & seen[U["part"]])
+                seen[U["part"]] |= set(rr)
+                nidx += len(rr)
+            assert len(set(used_slots)) == len(used_slots)  # plain stores: one writer per slot and unit
+            ovf = sorted(x for x in used_slots if x >= OVF_BASE)
+            assert ovf == list(range(OVF_BASE, OVF_BASE + nov))
+            regular = set(x for x in used_slots if x < WINDOW)
+            assert set(parents[:nov].tolist()) <= regular  # a further piece follows a first piece in the same unit
+            assert nidx == int(U["nidx"]) and len(used_slots) == int(U["npieces"])
+            stored += nidx
+    assert next_off * ALIGN == 2 * len(stream)
+    assert stored == info.stored_rows and pieces == info.segments
 
 
 @pytest.mark.parametrize("rows,cols,k,kind,seed", CASES)
@@ -230,7 +254,7 @@ def walk(h, S, v):
     """numpy mirror of the kernel's traversal of the packed streams (int64 arithmetic)."""
     info = h.info
     rows, cols, k, kw = info.rows, info.cols, info.k, info.lo_bits
-    units, entries, slots, blk = S["units"], S["entries"], S["slots"], S["blk_unit"]
+    units, stream, blk = S["units"], S["stream"], S["blk_unit"]
     vl = np.concatenate([np.asarray(v, dtype=np.int64), [0]])
     out = np.zeros(cols, dtype=np.int64)
     value_bits = np.array([[(j >> b) & 1 for b in range(9)] for j in range(WINDOW)], dtype=np.int64)
@@ -238,32 +262,27 @@ def walk(h, S, v):
         comb = np.zeros((2, 16), dtype=np.int64)
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
-            nsl8 = 8 * (-(-int(U["npieces"]) // 8))
-            acc = np.zeros(TILE, dtype=np.int64)
-            p = int(U["entry_off"]) * 8
-            for t in range(int(U["nt_main"])):  # wide diagonals: 8 ranks per lane
-                n = 8 * int(U["cnt8"][t])
-                acc[:n] += vl[entries[p : p + n].astype(int)]
-                p += n
-            assert p == (int(U["entry_off"]) + int(U["main_granules"])) * 8
-            tacc = np.zeros(64, dtype=np.int64)
-            for t in range(int(U["nt_main"]), int(U["nt"])):  # tail diagonals: lane l serves rank l
-                n = int(U["cnt8"][t])
-                tacc[:n] += vl[entries[p : p + n].astype(int)]
-                p += n
-            so = int(U["slot_off"]) * 8
+            pos = unit_positions(stream, U)
+            hdr = (int(U["hdr_hi"]) << 32) | int(U["hdr_lo"])
             win = np.zeros(WIN_SLOTS, dtype=np.int64)
-            win[slots[so : so + nsl8].astype(int)] = acc[:nsl8]
-            ntail = int(U["cnt8"][int(U["nt_main"])]) if int(U["nt_main"]) < int(U["nt"]) else 0
-            tslots = slots[so : so + ntail].astype(int)
-            assert len(set(tslots.tolist())) == ntail
-            win[tslots] += tacc[:ntail]
+            acc = np.zeros(LANES, dtype=np.int64)
+            slot = WINDOW + (np.arange(LANES) & (DUMMY - 1))
+            # (the kernel also gathers at the parent positions, into a dummy slot that is never read)
+            for p in range(-(-int(U["nov"]) // LANES), int(U["npos"])):
+                if (hdr >> p) & 1:
+                    win[slot] = acc
+                    slot = pos[p].copy()
+                    acc[:] = 0
+                else:
+                    acc += vl[pos[p]]
+            win[slot] = acc
             r = win[:WINDOW] @ value_bits
             tot = win[:WINDOW].sum()
-            for o in range(int(U["nov"])):
-                par = int(slots[so + nsl8 + o])
+            nov = int(U["nov"])
+            parents = pos[: -(-nov // LANES)].reshape(-1)
+            for o in range(nov):
                 val = win[OVF_BASE + o]
-                r = r + val * value_bits[par]
+                r = r + val * value_bits[int(parents[o])]
                 tot += val
             for bit in range(k):
                 t_ = r[bit] if bit < kw else (tot if (int(U["window"]) >> (bit - kw)) & 1 else 0)
@@ -283,12 +302,35 @@ def test_walk_over_packed_streams_gives_the_product(rows, cols, k, kind, seed):
     assert np.array_equal(got, dense.matvec_i8(A, v))
 
 
+def test_long_segments_are_cut_and_big_windows_split_into_units():
+    g = rng(5)
+    # 4000 rows, block width 3: seven segments of about 500 rows -> many pieces per segment
+    A = g.integers(0, 2, size=(4000, 6)).astype(np.int8)
+    with HostIndex(A, 3) as h:
+        S = R.rsr_host_streams(h.x)
+        check_streams(h, S)
+        assert S["units"]["nov"].max() > 0 and h.info.segments > 2 * 7 * 2
+        assert 2 * h.info.stored_rows > 0.85 * h.info.index_bytes  # long segments still fill the lanes
+    # 60000 equal rows: one segment spread over several units of the same window
+    A = np.ones((60000, 2), np.int8)
+    with HostIndex(A, 2) as h:
+        S = R.rsr_host_streams(h.x)
+        check_streams(h, S)
+        assert len(S["units"]) >= 60000 // (47 * 64) and np.all(S["units"]["window"] == 0)
+        assert 2 * h.info.stored_rows > 0.9 * h.info.index_bytes
+    # short segments only: nothing is cut more than once
+    A = g.integers(0, 2, size=(1500, 9)).astype(np.int8)
+    with HostIndex(A, 9) as h:
+        S = R.rsr_host_streams(h.x)
+        assert h.info.segments < 1.5 * 511
+
+
 @pytest.mark.parametrize("name", ["ones", "zeros", "identity", "equal_rows", "bin_k", "two_patterns"])
 def test_degenerate_matrices(name):
     g = rng(77)
     rows, cols, k = 3000, 24, 6
     if name == "ones":
-        A = np.ones((rows, cols), np.int8)          # one segment of 3000 rows per block: many cut pieces
+        A = np.ones((rows, cols), np.int8)          # one segment of 3000 rows per block: many pieces
     elif name == "zeros":
         A = np.zeros((rows, cols), np.int8)         # nothing stored, outputs still written
     elif name == "identity":
