@@ -45,7 +45,7 @@ class RsrInfo(ctypes.Structure):
 # numpy view of the 32-byte unit descriptors (csrc/rsr_format.h)
 UNIT_DTYPE = np.dtype(
     [
-        ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("nov", "u1"),
+        ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("npar", "u1"),
         ("units_in_block", "<u2"), ("npos", "u1"), ("ngroups", "u1"),
         ("hdr_lo", "<u4"), ("hdr_hi", "<u4"), ("nidx", "<u4"), ("npieces", "<u4"),
     ]

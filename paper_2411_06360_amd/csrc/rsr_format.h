@@ -21,9 +21,12 @@
 //     piece of a segment delivers its sum to the segment's own slot of the window; every further
 //     piece of that segment gets an overflow slot of its own, and the unit lists the segment
 //     value ("parent") of each overflow slot: the fold adds an overflow sum wherever its parent's
-//     bits say so, which is the same as adding it to the parent first.
+//     bits say so, which is the same as adding it to the parent first.  Overflow slot x is folded
+//     by lane x % 64, whose 16-lane row stands for the value bits 7 and 8: x is chosen so that
+//     (x % 64) / 16 == parent >> 7.  Unused overflow slots below the highest one in use have the
+//     null index as parent.
 //   * The unit's stream is a sequence of positions; a position holds one uint16 per lane.  It
-//     starts with 0, 1 or 2 parent positions (lane x of parent position c: the parent of overflow
+//     starts with 0 to 4 parent positions (lane x of parent position c: the parent of overflow
 //     slot 64c + x).  Then the groups follow: a header position and n index positions (n = the
 //     group's longest piece).  The header names, per lane, the window slot that receives the
 //     lane's sum for the group; lanes without a piece name a dummy slot.  An index position holds
@@ -52,9 +55,9 @@ constexpr int kLanes = 64;             // wavefront width
 constexpr int kMaxWindowBits = 9;      // window = 2^kw values, kw = min(k, 9)
 constexpr int kWindow = 1 << kMaxWindowBits;   // LDS slots of a window (always allocated in full)
 constexpr int kDummySlots = 8;         // slot ids kWindow .. kWindow+7 swallow lanes without a piece
-constexpr int kMaxOverflow = 128;      // overflow slots per unit (ids kOverflowBase ..)
+constexpr int kMaxOverflow = 256;      // overflow slots per unit (ids kOverflowBase ..), a quarter per row class
 constexpr int kOverflowBase = kWindow + kDummySlots;
-constexpr int kWindowSlots = kOverflowBase + kMaxOverflow;  // 648 accumulators per wavefront
+constexpr int kWindowSlots = kOverflowBase + kMaxOverflow;  // 776 accumulators per wavefront
 constexpr int kGranulePositions = 8;   // positions per 16-byte granule
 constexpr int kMaxGranules = 6;        // full granules of a unit at most
 constexpr int kMaxPositions = kMaxGranules * kGranulePositions;  // 48
@@ -69,7 +72,7 @@ struct alignas(16) Unit {
   uint32_t block;           // column block
   uint16_t window;          // window index inside the block: value >> kw
   uint8_t part;             // 0: B(1) (or binary B), 1: B(2)
-  uint8_t nov;              // overflow slots in use, <= kMaxOverflow; parent positions = ceil(nov / 64)
+  uint8_t npar;             // parent positions, 0 .. 4: the overflow slots 0 .. 64*npar-1 may be in use
   uint16_t units_in_block;  // units of this unit's column block (all parts and windows)
   uint8_t npos;             // positions in the stream: even, <= kMaxPositions
   uint8_t ngroups;          // groups = header positions

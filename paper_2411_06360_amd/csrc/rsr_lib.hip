@@ -29,6 +29,7 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/rsr.h"
 #include "rsr_format.h"
@@ -181,6 +182,21 @@ __device__ __forceinline__ AT row_sums_of_eight(const AT (&v)[8], int lane) {
   return y + dpp_get<0x128, 0xf, 0xf>(y);  // row_ror:8 is lane xor 8 inside a row
 }
 
+// Lane swaps of a value with itself, in assembly: the compiler takes the two results of the swap
+// builtins for equal when they are combined as floats.  (The s_nop covers the wait states a lane
+// swap needs after a vector write of its operands.)
+struct Swapped { uint32_t x, y; };
+__device__ __forceinline__ Swapped swap32(uint32_t v) {  // .x: lanes 0-31 twice, .y: lanes 32-63 twice
+  Swapped r{v, v};
+  asm volatile("s_nop 1\n v_permlane32_swap_b32 %0, %1" : "+v"(r.x), "+v"(r.y));
+  return r;
+}
+__device__ __forceinline__ Swapped swap16(uint32_t v) {  // .x: rows 0,0,2,2 of v, .y: rows 1,1,3,3
+  Swapped r{v, v};
+  asm volatile("s_nop 1\n v_permlane16_swap_b32 %0, %1" : "+v"(r.x), "+v"(r.y));
+  return r;
+}
+
 template <typename VT> struct Acc;
 template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
@@ -278,7 +294,7 @@ __device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, 
 // The scalar fields of a unit descriptor (wavefront-uniform); its 8 dwords sit in lanes 0..7 of dw.
 struct Desc {
   uint32_t stream_off, block, hdr_lo, hdr_hi;
-  int window, part, nov, units_in_block, npos;
+  int window, part, npar, units_in_block, npos;
 };
 __device__ __forceinline__ Desc decode(uint32_t dw) {
   Desc d;
@@ -287,7 +303,7 @@ __device__ __forceinline__ Desc decode(uint32_t dw) {
   const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 2), w3 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 3);
   d.window = (int)(w2 & 0xffffu);
   d.part = (int)((w2 >> 16) & 0xffu);
-  d.nov = (int)(w2 >> 24);
+  d.npar = (int)(w2 >> 24);
   d.units_in_block = (int)(w3 & 0xffffu);
   d.npos = (int)((w3 >> 16) & 0xffu);
   d.hdr_lo = (uint32_t)__builtin_amdgcn_readlane((int)dw, 4);
@@ -354,6 +370,21 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     }
   };
 
+  // The activation vector is staged first: its loads go out before anything else so that they do
+  // not queue behind the (much larger) first stream loads of the other wavefronts.
+  const VT* __restrict__ v = vin + (int64_t)b * p.rows;
+  constexpr int per16 = 16 / (int)sizeof(VT);
+  const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
+  const uint4* v16 = reinterpret_cast<const uint4*>(v);
+  constexpr int kEarly = 4;  // 16-byte pieces per thread fetched before the descriptors
+  uint4 sv[kEarly];
+#pragma unroll
+  for (int j = 0; j < kEarly; ++j) {
+    const int i = tid + j * (int)blockDim.x;
+    sv[j] = make_uint4(0, 0, 0, 0);
+    if (i < n16) sv[j] = v16[i];
+  }
+
   bool first_round = true;
   for (int rb0 = blk_begin; rb0 < blk_end;) {
     // ---- round set-up.  A round covers as many consecutive blocks as there are completion
@@ -363,23 +394,27 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       bu[tid] = blk_unit[blk < blk_end ? blk : blk_end];
     }
     if (tid < p.nslot) done[tid] = 0;
-    if (tid == 0) *ctr = (unsigned)nwaves;  // the first unit of every wavefront is fixed: u_begin + wave
-    // first unit of this wavefront: descriptor and stream loads go out before the barrier
+    // the first two units of every wavefront are fixed (u_begin + wave, u_begin + wave + nwaves), so
+    // that their descriptors can be fetched before the barrier; later ones come from the counter
+    if (tid == 0) *ctr = 2u * (unsigned)nwaves;
     const uint32_t u_begin = blk_unit[rb0];
-    const uint32_t guess = u_begin + (uint32_t)wave;
-    uint32_t dw = unit_words[(size_t)(guess < (uint32_t)p.nunits ? guess : 0u) * 8 + (lane & 7)];
     if (first_round) {
-      // stage the activation vector; vl[rows] = 0 serves the null row index
-      const VT* __restrict__ v = vin + (int64_t)b * p.rows;
-      constexpr int per16 = 16 / (int)sizeof(VT);
-      const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
-      const uint4* v16 = reinterpret_cast<const uint4*>(v);
+      // vl[rows] = 0 serves the null row index.  (Written before the descriptor loads go out:
+      // loads return in order, so nothing here waits for those.)
       uint4* l16 = reinterpret_cast<uint4*>(vl);
-      for (int i = tid; i < n16; i += blockDim.x) l16[i] = v16[i];
+#pragma unroll
+      for (int j = 0; j < kEarly; ++j) {
+        const int i = tid + j * (int)blockDim.x;
+        if (i < n16) l16[i] = sv[j];
+      }
+      for (int i = tid + kEarly * (int)blockDim.x; i < n16; i += blockDim.x) l16[i] = v16[i];
       for (int i = n16 * per16 + tid; i < p.rows; i += blockDim.x) vl[i] = v[i];
       if (tid == 0) vl[p.rows] = (VT)0;
       first_round = false;
     }
+    auto early_desc = [&](uint32_t u) { return unit_words[(size_t)(u < (uint32_t)p.nunits ? u : 0u) * 8 + (lane & 7)]; };
+    const uint32_t dw = early_desc(u_begin + (uint32_t)wave);
+    uint32_t dw1 = early_desc(u_begin + (uint32_t)(wave + nwaves));
     Desc D = decode(dw);
     issue(D.stream_off, D.npos, eA, tA);
     __syncthreads();
@@ -404,8 +439,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       return unit_words[(size_t)(ixq < n_tot ? u_begin + ixq : 0u) * 8 + (lane & 7)];
     };
     uint32_t ix = (uint32_t)wave;
-    uint32_t ix1 = (ix < n_tot) ? take() : n_tot;
-    uint32_t dw1 = fetch_desc(ix1);
+    uint32_t ix1 = (uint32_t)(wave + nwaves);
 
     // One unit from buffer (e, et); the next unit's stream goes into (en, etn) first.
     auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[3], uint32_t (&en)[NG][4], uint32_t (&etn)[3]) {
@@ -418,7 +452,8 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
         uint4* w16 = reinterpret_cast<uint4*>(win);
-        for (int i = lane; i < rsr::kWindowSlots / 4; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
+        const int n16w = (rsr::kOverflowBase + 64 * D.npar) / 4;  // the window, the dummies, the overflow slots in use
+        for (int i = lane; i < n16w; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
       }
       AT a = (AT)0;
       uint32_t sa = winbase + (uint32_t)(rsr::kWindow + (lane & (rsr::kDummySlots - 1))) * 4u;  // nothing to deliver yet
@@ -462,37 +497,44 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
       for (int beta = 0; beta < 4; ++beta) vals[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
       vals[7] = x;
-      AT ov7 = (AT)0, ov8 = (AT)0, ovt = (AT)0;
-      if (D.nov > 0) {
+      if (D.npar > 0) {
         // further pieces of segments: their sums sit in overflow slots and count wherever the bits of
-        // the segment's value (the parent, listed in the first positions of the stream) say so
-        const uint32_t parw = (full > 0) ? e[0][0] : et[0];
+        // the segment's value (the parent, listed in the first positions of the stream) say so.
+        // Bits 0..6 are picked here; the lane that folds an overflow slot lies in the 16-lane row
+        // that stands for the parent's bits 7 and 8, so adding to the lane's total settles those.
+        const uint32_t parw0 = (full > 0) ? e[0][0] : et[0];
+        const uint32_t parw1 = (full > 0) ? e[0][1] : et[1];
 #pragma unroll
         for (int c = 0; c < rsr::kMaxOverflow / 64; ++c) {
-          if (c * 64 < D.nov) {
+          if (c < D.npar) {
             const AT val = win[rsr::kOverflowBase + c * 64 + lane];  // unused overflow slots hold 0
-            const uint32_t par = (c == 0) ? (parw & 0xffffu) : (parw >> 16);
+            const uint32_t pw = (c < 2) ? parw0 : parw1;
+            const uint32_t par = (c & 1) ? (pw >> 16) : (pw & 0xffffu);
 #pragma unroll
             for (int beta = 0; beta < 7; ++beta) vals[beta] += ((par >> beta) & 1) ? val : (AT)0;
-            ov7 += wave_sum_to_lane63<AT>(((par >> 7) & 1) ? val : (AT)0);
-            ov8 += wave_sum_to_lane63<AT>(((par >> 8) & 1) ? val : (AT)0);
-            ovt += wave_sum_to_lane63<AT>(val);
+            vals[7] += val;
           }
         }
-        ov7 = read_lane<AT>(ov7, 63); ov8 = read_lane<AT>(ov8, 63); ovt = read_lane<AT>(ovt, 63);
       }
-      const AT rowsum = row_sums_of_eight<AT>(vals, lane);
-      win[lane] = rowsum;  // the window has been read: its first 64 slots carry the four rows across
+      // Sums over the 16 lanes of each row, then across the four rows with lane swaps: total
+      // (all rows), value bit 7 (rows 1 and 3) and value bit 8 (rows 2 and 3).
+      const uint32_t rowsum = __builtin_bit_cast(uint32_t, row_sums_of_eight<AT>(vals, lane));
+      const Swapped h32 = swap32(rowsum);                                              // .x: rows 0,1,0,1  .y: rows 2,3,2,3
+      const AT s02_13 = __builtin_bit_cast(AT, h32.x) + __builtin_bit_cast(AT, h32.y);  // rows 0+2, 1+3, 0+2, 1+3
+      const Swapped t16 = swap16(__builtin_bit_cast(uint32_t, s02_13));                // .x: 0+2 everywhere  .y: 1+3 everywhere
+      const Swapped b16 = swap16(h32.y);                                               // .x: row 2 everywhere  .y: row 3
+      const AT total = __builtin_bit_cast(AT, t16.x) + __builtin_bit_cast(AT, t16.y);
+      const AT bit7 = __builtin_bit_cast(AT, t16.y);
+      const AT bit8 = __builtin_bit_cast(AT, b16.x) + __builtin_bit_cast(AT, b16.y);
       // ---- record, and completion of the block: lanes 0..7 finish the sums ----
       const int slot = (int)D.block - rb0;
       unsigned before = 0;
       if (lane < 8) {
-        const AT r0 = win[lane], r1 = win[16 + lane], r2 = win[32 + lane], r3 = win[48 + lane];
         AT* rr = rec + (size_t)ix * rsr::kRecordWords;
-        rr[lane == 7 ? 9 : lane] = ((r0 + r1) + (r2 + r3)) + (lane == 7 ? ovt : (AT)0);
+        rr[lane == 7 ? 9 : lane] = total;
         if (lane == 7) {
-          rr[7] = (r1 + r3) + ov7;  // lane bit 4 = rows 1 and 3 = value bit 7
-          rr[8] = (r2 + r3) + ov8;  // lane bit 5 = rows 2 and 3 = value bit 8
+          rr[7] = bit7;  // lane bit 4 = rows 1 and 3 = value bit 7
+          rr[8] = bit8;  // lane bit 5 = rows 2 and 3 = value bit 8
           rr[10] = __builtin_bit_cast(AT, (uint32_t)((D.part << 16) | D.window));
           before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
         }

@@ -21,8 +21,8 @@ struct BlockOut {
   int64_t stored_rows = 0, segments = 0, header_positions = 0;
 };
 
-// Longest piece: its group (header + rows) and two parent positions have to fit into one unit.
-constexpr int kMaxPieceRows = kMaxPositions - 3;
+// Longest piece: its group (header + rows) and all parent positions have to fit into one unit.
+constexpr int kMaxPieceRows = kMaxPositions - 1 - kMaxOverflow / kLanes;
 // Cost of a work unit beyond its positions (descriptor, window clearing, fold), in positions.
 constexpr int kUnitCost = 3;
 
@@ -77,7 +77,7 @@ void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std:
   u.block = block;
   u.window = (uint16_t)window;
   u.part = (uint8_t)part;
-  u.nov = (uint8_t)nov;
+  u.npar = (uint8_t)ceil_div(nov, kLanes);
   u.npos = (uint8_t)npos;
   u.ngroups = (uint8_t)ngroups;
   u.hdr_lo = (uint32_t)hdr;
@@ -168,17 +168,23 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
     for (const Piece& p : S->pieces) S->sorted[bucket[kMaxPieceRows - p.len]++] = p;
 
     // ---- units: consecutive groups while positions and overflow slots last ----
+    // Overflow slot x sits in lane x % 64 of the fold; the kernel adds its sum to that lane's total,
+    // so the lane's 16-lane row (which stands for value bits 7 and 8) has to match the parent's:
+    // class c = parent >> 7 owns the overflow slots 64i + 16c .. 64i + 16c + 15, i = 0 .. 3.
     const int np = (int)S->sorted.size();
     S->unit_slot.resize((size_t)np);
     int first = 0;        // first piece of the unit being filled
     int posn = 0;         // its positions without the parent positions
-    S->parents.clear();
+    int cls_used[4] = {0, 0, 0, 0};
+    S->parents.clear();   // parent of every overflow slot up to the highest one in use (null = unused)
     S->seen.assign(W, 0);
+    auto ovf_index = [](int cls, int n) { return (n / 16) * kLanes + 16 * cls + n % 16; };
     auto flush_unit = [&](int end) {
       emit_unit(&S->sorted[(size_t)first], &S->unit_slot[(size_t)first], end - first, S->parents, S->sigma, block, w, part,
                 null_index, S->positions, out);
       first = end;
       posn = 0;
+      for (int& c : cls_used) c = 0;
       S->parents.clear();
       S->seen.assign(W, 0);
     };
@@ -186,13 +192,20 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
       const int cnt = std::min(kLanes, np - r0);
       const int need = 1 + (int)S->sorted[(size_t)r0].len;
       for (int attempt = 0;; ++attempt) {
-        int extra = 0;  // pieces of this group whose segment already has a piece in the unit (or in this group)
+        // pieces of this group whose segment already has a piece in the unit (or earlier in this group)
+        int extra[4] = {0, 0, 0, 0};
         for (int l = 0; l < cnt; ++l) {
           const uint16_t sl = S->sorted[(size_t)(r0 + l)].slot;
-          if (S->seen[sl]) ++extra; else S->seen[sl] = 2;  // 2: tentatively, by this group
+          if (S->seen[sl]) ++extra[(sl >> 7) & 3]; else S->seen[sl] = 2;  // 2: tentatively, by this group
         }
-        const int nov = (int)S->parents.size() + extra;
-        const bool fits = nov <= kMaxOverflow && posn + need + ceil_div(nov, kLanes) <= kMaxPositions;
+        bool fits = true;
+        int top = (int)S->parents.size();
+        for (int c = 0; c < 4; ++c) {
+          const int n = cls_used[c] + extra[c];
+          if (n > kMaxOverflow / 4) fits = false;
+          else if (extra[c]) top = std::max(top, ovf_index(c, n - 1) + 1);
+        }
+        if (posn + need + ceil_div(top, kLanes) > kMaxPositions) fits = false;
         if (fits || attempt == 1) {
           for (int l = 0; l < cnt; ++l) {
             Piece& pc = S->sorted[(size_t)(r0 + l)];
@@ -200,8 +213,11 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
               S->seen[pc.slot] = 1;
               S->unit_slot[(size_t)(r0 + l)] = pc.slot;
             } else {
-              S->unit_slot[(size_t)(r0 + l)] = (uint16_t)(kOverflowBase + S->parents.size());
-              S->parents.push_back(pc.slot);
+              const int c = (pc.slot >> 7) & 3;
+              const int x = ovf_index(c, cls_used[c]++);
+              if ((int)S->parents.size() <= x) S->parents.resize((size_t)x + 1, null_index);
+              S->parents[(size_t)x] = pc.slot;
+              S->unit_slot[(size_t)(r0 + l)] = (uint16_t)(kOverflowBase + x);
             }
           }
           posn += need;
@@ -390,8 +406,8 @@ int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32
     if (u.npos > kMaxPositions || (u.npos & 1)) { *err = "corrupt unit: position count"; return -1; }
     const uint16_t* us = &P.stream[(size_t)u.stream_off * (kStreamAlign / sizeof(uint16_t))];
     const uint64_t hdr = ((uint64_t)u.hdr_hi << 32) | u.hdr_lo;
-    const int npar = (u.nov + kLanes - 1) / kLanes;
-    if (u.nov > kMaxOverflow || npar > u.npos) { *err = "corrupt unit: overflow slots"; return -1; }
+    const int npar = u.npar;
+    if (npar > kMaxOverflow / kLanes || npar > u.npos) { *err = "corrupt unit: overflow slots"; return -1; }
     uint16_t slot[kLanes];
     for (int l = 0; l < kLanes; ++l) slot[l] = (uint16_t)kWindow;
     for (int p = npar; p < u.npos; ++p) {
@@ -406,8 +422,9 @@ int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32
         uint32_t sl = slot[l];
         if (sl >= (uint32_t)kOverflowBase) {  // a further piece of a segment: filed under its parent
           const uint32_t o = sl - kOverflowBase;
-          if (o >= u.nov) { *err = "corrupt unit: overflow slot out of range"; return -1; }
+          if (o >= (uint32_t)npar * kLanes) { *err = "corrupt unit: overflow slot out of range"; return -1; }
           sl = stream_at(us, u.npos, (int)(o / kLanes), (int)(o % kLanes));
+          if (sl < (uint32_t)kWindow && ((sl >> 7) & 3) != ((o % kLanes) >> 4)) { *err = "corrupt unit: overflow slot in the wrong row"; return -1; }
         }
         if (sl >= (uint32_t)kWindow) { *err = "corrupt unit: row in a dummy slot"; return -1; }
         const uint32_t value = (((uint32_t)u.window << P.kw) + sl) >> shift;

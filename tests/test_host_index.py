@@ -18,7 +18,7 @@ from oracle import dense, steps
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 # layout constants of csrc/rsr_format.h
-WINDOW, DUMMY, OVF_BASE, MAX_OVF, WIN_SLOTS, LANES, MAX_POS, ALIGN = 512, 8, 520, 128, 648, 64, 48, 256
+WINDOW, DUMMY, OVF_BASE, MAX_OVF, WIN_SLOTS, LANES, MAX_POS, ALIGN = 512, 8, 520, 256, 776, 64, 48, 256
 
 
 def rng(seed):
@@ -167,7 +167,7 @@ def unit_positions(stream, U):
 def unit_groups(U, pos):
     """(parent positions, [(header position, index positions)]) of the unit."""
     hdr = (int(U["hdr_hi"]) << 32) | int(U["hdr_lo"])
-    npar = -(-int(U["nov"]) // LANES)
+    npar = int(U["npar"])
     heads = [p for p in range(int(U["npos"])) if (hdr >> p) & 1]
     assert hdr >> int(U["npos"]) == 0 and len(heads) == int(U["ngroups"])
     if heads:
@@ -198,14 +198,15 @@ def check_streams(h, S):
             assert U["block"] == b and U["part"] < info.parts
             assert U["units_in_block"] == blk[b + 1] - blk[b]
             assert U["window"] < (1 << (k - kw))
-            npos, nov = int(U["npos"]), int(U["nov"])
-            assert npos % 2 == 0 and npos <= MAX_POS and nov <= MAX_OVF
+            npos = int(U["npos"])
+            assert npos % 2 == 0 and npos <= MAX_POS and int(U["npar"]) <= MAX_OVF // LANES
             assert int(U["stream_off"]) == next_off  # unit streams are back to back, 256-byte aligned
             next_off += npos * LANES * 2 // ALIGN
             pos = unit_positions(stream, U)
             npar, groups = unit_groups(U, pos)
-            parents = pos[:npar].reshape(-1)
-            assert np.all(parents[:nov] < (1 << kw)) and np.all(parents[nov:] == rows)
+            parents = pos[:npar].reshape(-1)  # parent of overflow slot x, or the null index if x is unused
+            assert np.all((parents < (1 << kw)) | (parents == rows))
+            in_use = np.flatnonzero(parents < (1 << kw)) if rows >= (1 << kw) else None
             used_slots = []
             nidx = 0
             last_len = None
@@ -223,7 +224,7 @@ def check_streams(h, S):
                 last_len = lens[owners][-1] if owners.any() else last_len
                 assert np.all(slots[~owners] >= WINDOW) and np.all(slots[~owners] < OVF_BASE)  # dummies
                 own = slots[owners]
-                assert np.all((own < (1 << kw)) | ((own >= OVF_BASE) & (own < OVF_BASE + nov)))
+                assert np.all((own < (1 << kw)) | ((own >= OVF_BASE) & (own < OVF_BASE + LANES * npar)))
                 # only the unit's last group may carry one all-null position (even position count)
                 assert lens[0] >= len(idxs) - (1 if head == groups[-1][0] else 0) and lens[0] >= 1
                 used_slots += own.tolist()
@@ -233,10 +234,16 @@ def check_streams(h, S):
                 seen[U["part"]] |= set(rr)
                 nidx += len(rr)
             assert len(set(used_slots)) == len(used_slots)  # plain stores: one writer per slot and unit
-            ovf = sorted(x for x in used_slots if x >= OVF_BASE)
-            assert ovf == list(range(OVF_BASE, OVF_BASE + nov))
+            ovf = sorted(x - OVF_BASE for x in used_slots if x >= OVF_BASE)
+            if in_use is not None:
+                assert ovf == in_use.tolist()  # exactly the overflow slots that have a parent
+            if npar:
+                assert ovf and ovf[-1] >= LANES * (npar - 1)  # no parent position without need
             regular = set(x for x in used_slots if x < WINDOW)
-            assert set(parents[:nov].tolist()) <= regular  # a further piece follows a first piece in the same unit
+            for x in ovf:
+                par = int(parents[x])
+                assert par in regular  # a further piece follows a first piece of its segment in the same unit
+                assert (x % LANES) // 16 == par >> 7  # folded by a lane in the row of the parent's bits 7, 8
             assert nidx == int(U["nidx"]) and len(used_slots) == int(U["npieces"])
             stored += nidx
     assert next_off * ALIGN == 2 * len(stream)
@@ -268,7 +275,8 @@ def walk(h, S, v):
             acc = np.zeros(LANES, dtype=np.int64)
             slot = WINDOW + (np.arange(LANES) & (DUMMY - 1))
             # (the kernel also gathers at the parent positions, into a dummy slot that is never read)
-            for p in range(-(-int(U["nov"]) // LANES), int(U["npos"])):
+            npar = int(U["npar"])
+            for p in range(npar, int(U["npos"])):
                 if (hdr >> p) & 1:
                     win[slot] = acc
                     slot = pos[p].copy()
@@ -278,12 +286,12 @@ def walk(h, S, v):
             win[slot] = acc
             r = win[:WINDOW] @ value_bits
             tot = win[:WINDOW].sum()
-            nov = int(U["nov"])
-            parents = pos[: -(-nov // LANES)].reshape(-1)
-            for o in range(nov):
+            parents = pos[:npar].reshape(-1)
+            for o in range(LANES * npar):
                 val = win[OVF_BASE + o]
-                r = r + val * value_bits[int(parents[o])]
-                tot += val
+                if val:  # unused overflow slots stay 0 (their parent is the null index)
+                    r = r + val * value_bits[int(parents[o])]
+                    tot += val
             for bit in range(k):
                 t_ = r[bit] if bit < kw else (tot if (int(U["window"]) >> (bit - kw)) & 1 else 0)
                 comb[int(U["part"]), bit] += t_
@@ -309,8 +317,8 @@ def test_long_segments_are_cut_and_big_windows_split_into_units():
     with HostIndex(A, 3) as h:
         S = R.rsr_host_streams(h.x)
         check_streams(h, S)
-        assert S["units"]["nov"].max() > 0 and h.info.segments > 2 * 7 * 2
-        assert 2 * h.info.stored_rows > 0.85 * h.info.index_bytes  # long segments still fill the lanes
+        assert S["units"]["npar"].max() > 0 and h.info.segments > 2 * 7 * 2
+        assert 2 * h.info.stored_rows > 0.75 * h.info.index_bytes  # long segments still fill the lanes
     # 60000 equal rows: one segment spread over several units of the same window
     A = np.ones((60000, 2), np.int8)
     with HostIndex(A, 2) as h:
