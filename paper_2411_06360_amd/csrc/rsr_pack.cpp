@@ -21,8 +21,6 @@ struct BlockOut {
   int64_t stored_rows = 0, segments = 0, header_positions = 0;
 };
 
-// Longest piece: its group (header + rows) and all parent positions have to fit into one unit.
-constexpr int kMaxPieceRows = kMaxPositions - 1 - kMaxOverflow / kLanes;
 // Cost of a work unit beyond its positions (descriptor, window clearing, fold), in positions.
 constexpr int kUnitCost = 3;
 
@@ -37,6 +35,33 @@ struct Scratch {
 };
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Longest piece: its group (header + rows) and all parent positions have to fit into one unit.
+constexpr int kMaxPieceRows = kMaxPositions - 1 - kMaxOverflow / kLanes;
+
+// Bipartite matching (augmenting paths) of the lanes l0 .. l0+31 to the 32 LDS banks: a lane can
+// take a bank if one of the rows it has left lies in it.
+struct BankMatch {
+  const uint16_t (*rows_of)[kMaxPieceRows];
+  const uint32_t* left;
+  int l0;
+  int bank_lane[32];   // lane matched to the bank, or -1
+  int lane_pick[32];   // index into rows_of[lane] of the matched row, or -1
+  bool seen_bank[32];
+  bool augment(int lane) {
+    for (uint32_t c = 0; c < left[lane]; ++c) {
+      const int bank = rows_of[lane][c] & 31;
+      if (seen_bank[bank]) continue;
+      seen_bank[bank] = true;
+      if (bank_lane[bank] < 0 || augment(bank_lane[bank])) {
+        bank_lane[bank] = lane;
+        lane_pick[lane - l0] = (int)c;
+        return true;
+      }
+    }
+    return false;
+  }
+};
 
 // One unit: pcs[first .. first+count) (sorted by descending length, count a multiple of 64 except
 // in the last unit of a window), their slots, and the parents of the overflow slots among them.
@@ -63,10 +88,52 @@ void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std:
     hdr |= 1ull << npos;
     uint16_t* h = add_position(0);
     for (int l = 0; l < kLanes; ++l) h[l] = (l < cnt) ? slot_ids[r0 + l] : (uint16_t)(kWindow + (l & (kDummySlots - 1)));
+    // The order of the rows inside a piece is free (they are summed).  It is chosen so that the 32
+    // lanes of each half of the wavefront, which the LDS serves together, read 32 different banks
+    // where possible (bank of a float activation = row mod 32): position after position, a maximum
+    // matching of lanes to banks over the rows each lane has left; a lane that stays unmatched takes
+    // the row whose bank is least used.
+    uint32_t left[kLanes];  // rows of the lane's piece not placed yet: rows_of[l][0 .. left)
+    uint16_t rows_of[kLanes][kMaxPieceRows];
+    for (int l = 0; l < cnt; ++l) {
+      left[l] = pcs[r0 + l].len;
+      for (uint32_t t = 0; t < left[l]; ++t) rows_of[l][t] = sigma[pcs[r0 + l].start + t];
+    }
     for (int t = 0; t < n; ++t) {
       uint16_t* e = add_position(null_index);
-      for (int l = 0; l < cnt; ++l)
-        if (t < pcs[r0 + l].len) { e[l] = sigma[pcs[r0 + l].start + t]; ++nidx; }
+      for (int half = 0; half < 2; ++half) {
+        const int l0 = half * 32, l1 = std::min(cnt, l0 + 32);
+        BankMatch m;
+        m.rows_of = &rows_of[0];
+        m.left = left;
+        m.l0 = l0;
+        for (int i = 0; i < 32; ++i) { m.bank_lane[i] = -1; m.lane_pick[i] = -1; }
+        // lanes with the fewest rows left (the highest lanes) go first
+        for (int l = l1 - 1; l >= l0; --l) {
+          if (left[l] == 0) continue;
+          for (bool& sb : m.seen_bank) sb = false;
+          m.augment(l);
+        }
+        const int* bank_lane = m.bank_lane;
+        const int* lane_pick = m.lane_pick;
+        uint8_t load[32] = {0};
+        for (int i = 0; i < 32; ++i) if (bank_lane[i] >= 0) load[i] = 1;
+        for (int l = l1 - 1; l >= l0; --l) {
+          if (left[l] == 0) continue;
+          uint32_t best;
+          if (lane_pick[l - l0] >= 0) {
+            best = (uint32_t)lane_pick[l - l0];
+          } else {
+            best = 0;
+            for (uint32_t c = 1; c < left[l]; ++c)
+              if (load[rows_of[l][c] & 31] < load[rows_of[l][best] & 31]) best = c;
+            ++load[rows_of[l][best] & 31];
+          }
+          e[l] = rows_of[l][best];
+          rows_of[l][best] = rows_of[l][--left[l]];
+          ++nidx;
+        }
+      }
     }
     ++ngroups;
   }
