@@ -352,22 +352,22 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   // wait for the current unit never waits for the next one.
   uint32_t eA[NG][4], eB[NG][4];
   uint32_t tA[3], tB[3];  // positions behind the last full granule: up to three rows of dwords
-  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
-    const int full = npos >> 3;
+  auto issue_granule = [&](uint32_t stream_off, int npos, int gq, uint32_t (&e)[NG][4]) {
     const unsigned char* us = stream + (size_t)stream_off * rsr::kStreamAlign;
+    const unsigned char* src = (gq < (npos >> 3)) ? us + gq * 1024 : stream;
+    const u32x4 x = load_granule(src + lane16);
+    e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
+  };
+  auto issue_pair = [&](uint32_t stream_off, int npos, int j, uint32_t (&et)[3]) {
+    const unsigned char* ut = stream + (size_t)stream_off * rsr::kStreamAlign + (size_t)(npos >> 3) * 1024;
+    const unsigned char* src = (j < ((npos & 7) >> 1)) ? ut + j * 256 : stream;
+    et[j] = load_pair(src + lane4);
+  };
+  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
 #pragma unroll
-    for (int gq = 0; gq < NG; ++gq) {
-      const unsigned char* src = (gq < full) ? us + gq * 1024 : stream;
-      const u32x4 x = load_granule(src + lane16);
-      e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
-    }
-    const int pairs = (npos & 7) >> 1;
-    const unsigned char* ut = us + (size_t)full * 1024;
+    for (int gq = 0; gq < NG; ++gq) issue_granule(stream_off, npos, gq, e);
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      const unsigned char* src = (j < pairs) ? ut + j * 256 : stream;
-      et[j] = load_pair(src + lane4);
-    }
+    for (int j = 0; j < 3; ++j) issue_pair(stream_off, npos, j, et);
   };
 
   // The activation vector is staged first: its loads go out before anything else so that they do
@@ -447,7 +447,8 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       const uint32_t dw2 = fetch_desc(ix2);
       Desc D1 = decode(dw1);
       if (ix1 >= n_tot) D1.npos = 0;
-      issue(D1.stream_off, D1.npos, en, etn);
+      // (its loads go out one by one between the steps below: a wavefront that issues a whole
+      // unit at once waits for room in the memory pipeline while it could be summing)
 
       // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
@@ -464,14 +465,17 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
           const uint32_t hb = ((gq < 4 ? D.hdr_lo : D.hdr_hi) >> (8 * (gq & 3))) & 0xffu;
           granule_step(hb, e[gq][0], e[gq][1], e[gq][2], e[gq][3], a, sa, winbase, vl);
         }
+        issue_granule(D1.stream_off, D1.npos, gq, en);
       }
       {
         const int pairs = (D.npos & 7) >> 1;
         const uint64_t hdr = ((uint64_t)D.hdr_hi << 32) | D.hdr_lo;
         const uint32_t tm = (uint32_t)(hdr >> (8 * full));
 #pragma unroll
-        for (int j = 0; j < 3; ++j)
+        for (int j = 0; j < 3; ++j) {
           if (j < pairs) pair_step((tm >> (2 * j)) & 3u, et[j], a, sa, winbase, vl);
+          issue_pair(D1.stream_off, D1.npos, j, etn);
+        }
       }
       *reinterpret_cast<AT*>(lds + sa) = a;  // the last group
 
