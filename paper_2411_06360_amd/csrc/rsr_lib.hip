@@ -354,14 +354,16 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   uint32_t tA[3], tB[3];  // positions behind the last full granule: up to three rows of dwords
   auto issue_granule = [&](uint32_t stream_off, int npos, int gq, uint32_t (&e)[NG][4]) {
     const unsigned char* us = stream + (size_t)stream_off * rsr::kStreamAlign;
-    const unsigned char* src = (gq < (npos >> 3)) ? us + gq * 1024 : stream;
-    const u32x4 x = load_granule(src + lane16);
+    const bool need = gq < (npos >> 3);
+    const unsigned char* src = need ? us + gq * 1024 : stream;
+    const u32x4 x = load_granule(src + (need ? lane16 : 0u));  // a load that is not needed: one address for all lanes
     e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
   };
   auto issue_pair = [&](uint32_t stream_off, int npos, int j, uint32_t (&et)[3]) {
     const unsigned char* ut = stream + (size_t)stream_off * rsr::kStreamAlign + (size_t)(npos >> 3) * 1024;
-    const unsigned char* src = (j < ((npos & 7) >> 1)) ? ut + j * 256 : stream;
-    et[j] = load_pair(src + lane4);
+    const bool need = j < ((npos & 7) >> 1);
+    const unsigned char* src = need ? ut + j * 256 : stream;
+    et[j] = load_pair(src + (need ? lane4 : 0u));
   };
   auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
 #pragma unroll
