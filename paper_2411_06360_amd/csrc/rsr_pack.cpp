@@ -193,13 +193,15 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
     int best_T = 1, best_cost = 0x7fffffff;
     for (int T = std::min<uint32_t>(longest, kMaxPieceRows); T >= 1; --T) {
       uint32_t hist[kMaxPieceRows + 1] = {0};
-      uint32_t nov = 0;
+      uint32_t nov = 0, nov_cls[4] = {0, 0, 0, 0};  // further pieces, also per row class (value bits 7, 8)
       for (uint32_t jl = jfirst; jl < W; ++jl) {
         const uint32_t c = S->off[j0 + jl + 1] - S->off[j0 + jl];
         if (!c) continue;
         hist[T] += c / (uint32_t)T;
         if (c % (uint32_t)T) ++hist[c % (uint32_t)T];
-        nov += (c + (uint32_t)T - 1) / (uint32_t)T - 1;
+        const uint32_t more = (c + (uint32_t)T - 1) / (uint32_t)T - 1;
+        nov += more;
+        nov_cls[(jl >> 7) & 3] += more;
       }
       // groups of 64 in descending length: a group costs its header and its longest piece
       int cost = 0;
@@ -213,8 +215,10 @@ void pack_part(int64_t rows, int k, int kw, uint32_t block, int part, Scratch* S
           n -= take;
         }
       }
-      cost += ceil_div((int)nov, kLanes);
-      const int units = std::max(ceil_div(cost, kMaxPositions - 2), ceil_div((int)nov, kMaxOverflow));
+      // parent positions: a row class has 16 overflow slots per position
+      const uint32_t cls_max = std::max(std::max(nov_cls[0], nov_cls[1]), std::max(nov_cls[2], nov_cls[3]));
+      cost += ceil_div((int)cls_max, kLanes / 4);
+      const int units = std::max(ceil_div(cost, kMaxPositions - 2), ceil_div((int)cls_max, kMaxOverflow / 4));
       cost += units * kUnitCost;
       if (cost < best_cost) { best_cost = cost; best_T = T; }
       if (nov > (uint32_t)8 * kMaxOverflow && cost > 2 * best_cost) break;  // shorter pieces only get worse
