@@ -72,6 +72,48 @@ def test_small_shapes_int8_exact_and_f32_close(rows, cols, k, kind):
             assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
 
 
+# ---- layout paths: many pieces per segment, several units per window, several rounds per workgroup ------
+LAYOUT = [
+    # name, rows, cols, k, what it exercises
+    ("equal_rows", 30000, 4, 2, "one segment of 30000 rows: ~700 pieces, 4 parent positions, >10 units of one window"),
+    ("seven_long_segments", 4000, 6, 3, "segments of ~500 rows: every unit full of pieces of the same few segments"),
+    ("skewed_lengths", 5000, 40, 10, "ternary with 70 % zeros: segment lengths from 1 to ~150 in one window"),
+    ("many_blocks", 200, 40000, 1, "40000 blocks: more than 64 blocks per workgroup, several rounds"),
+    ("wide_k16", 3000, 64, 16, "k = 16: 128 windows per block, mostly empty"),
+    ("two_patterns_ternary", 9000, 30, 10, "rows drawn from two patterns: two segments of ~4500 rows per part"),
+]
+
+
+@pytest.mark.parametrize("name,rows,cols,k,what", LAYOUT)
+def test_layout_paths(name, rows, cols, k, what):
+    g = rng(len(name) * 131 + rows)
+    if name == "equal_rows":
+        A = np.ones((rows, cols), np.int8)
+    elif name == "skewed_lengths":
+        A = g.choice(np.array([-1, 0, 1], np.int8), size=(rows, cols), p=[0.15, 0.7, 0.15])
+    elif name == "two_patterns_ternary":
+        A = g.integers(-1, 2, size=(2, cols)).astype(np.int8)[g.integers(0, 2, size=rows)]
+    elif name in ("seven_long_segments", "many_blocks"):
+        A = g.integers(0, 2, size=(rows, cols)).astype(np.int8)
+    else:
+        A = g.integers(-1, 2, size=(rows, cols)).astype(np.int8)
+    note(f"layout {name}: {what}")
+    with DeviceIndex(A, k) as d:
+        for batch in (1, 2):
+            v8 = g.integers(-127, 128, size=(batch, rows), dtype=np.int8)
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+            vf = g.standard_normal((batch, rows)).astype(np.float32)
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+        if name == "equal_rows":  # closed form: every output is the sum of v
+            v1 = np.ones((1, rows), np.int8)
+            assert np.all(d.matvec(v1) == rows)
+    if name == "equal_rows":  # the int8 path takes twice the rows (a float vector of 60000 does not fit the LDS)
+        A2 = np.ones((60000, 2), np.int8)
+        with DeviceIndex(A2, 2) as d:
+            v8 = g.integers(-127, 128, size=(1, 60000), dtype=np.int8)
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A2, v8))
+
+
 def test_k_invariance_same_matrix_every_k():
     g = rng(41)
     A = g.integers(-1, 2, size=(600, 70)).astype(np.int8)
