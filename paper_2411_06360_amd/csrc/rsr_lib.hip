@@ -552,16 +552,31 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
         // with bit `bit` set".  Bits below kw are in the unit records; a higher bit sees only
         // window totals (the remaining levels of the fold act on the windows' sums).
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // the records were written by this workgroup
-        const int bit = lane & 15, q = lane >> 4;
-        const AT* rr = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
+        // (the two halves of the wavefront take every other record, two records per step, so that
+        // four LDS reads are in flight instead of one dependent pair)
+        const int bit = lane & 15, q = (lane >> 4) & 1, half = lane >> 5;
+        const AT* base = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
         const int word = (bit < p.kw) ? bit : 9;
-        AT sum = (AT)0;
-        for (int j = 0; j < D.units_in_block; ++j, rr += rsr::kRecordWords) {
-          const uint32_t meta = __builtin_bit_cast(uint32_t, rr[10]);
-          const AT t = rr[word];
+        auto term = [&](uint32_t meta, AT t) {
           const bool use = ((int)(meta >> 16) == q) && (bit < p.kw || (((meta & 0xffffu) >> (bit - p.kw)) & 1u));
-          sum += use ? t : (AT)0;
+          return use ? t : (AT)0;
+        };
+        AT sum_a = (AT)0, sum_b = (AT)0;
+        int j = half;
+        for (; j + 2 < D.units_in_block; j += 4) {
+          const AT* ra = base + (size_t)j * rsr::kRecordWords;
+          const AT* rb = ra + 2 * rsr::kRecordWords;
+          const uint32_t ma = __builtin_bit_cast(uint32_t, ra[10]), mb = __builtin_bit_cast(uint32_t, rb[10]);
+          const AT ta = ra[word], tb = rb[word];
+          sum_a += term(ma, ta);
+          sum_b += term(mb, tb);
         }
+        if (j < D.units_in_block) {
+          const AT* ra = base + (size_t)j * rsr::kRecordWords;
+          sum_a += term(__builtin_bit_cast(uint32_t, ra[10]), ra[word]);
+        }
+        AT sum = sum_a + sum_b;
+        sum += __shfl_xor(sum, 32, 64);
         const AT minus = __shfl(sum, lane + 16, 64);  // part 1 sits 16 lanes up
         const AT res = sum - minus;                   // Proposition 2.1: v.B(1) - v.B(2)
         // value bit `bit` belongs to column k-1-bit of the block (first column most significant)
