@@ -47,7 +47,7 @@ UNIT_DTYPE = np.dtype(
     [
         ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("npar", "u1"),
         ("units_in_block", "<u2"), ("npos", "u1"), ("ngroups", "u1"),
-        ("hdr_lo", "<u4"), ("hdr_hi", "<u4"), ("nidx", "<u4"), ("npieces", "<u4"),
+        ("hdr_lo", "<u4"), ("hdr_hi", "<u2"), ("index_in_block", "<u2"), ("nidx", "<u4"), ("npieces", "<u4"),
     ]
 )
 assert UNIT_DTYPE.itemsize == 32

@@ -77,7 +77,8 @@ struct alignas(16) Unit {
   uint8_t npos;             // positions in the stream: even, <= kMaxPositions
   uint8_t ngroups;          // groups = header positions
   uint32_t hdr_lo;          // bit p: position p is a header (positions 0..31)
-  uint32_t hdr_hi;          // positions 32..47
+  uint16_t hdr_hi;          // positions 32..47
+  uint16_t index_in_block;  // this unit's number among the units of its block
   uint32_t nidx;            // real (non-null) row indices in the unit
   uint32_t npieces;         // pieces in the unit
 };

@@ -294,7 +294,7 @@ __device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, 
 // The scalar fields of a unit descriptor (wavefront-uniform); its 8 dwords sit in lanes 0..7 of dw.
 struct Desc {
   uint32_t stream_off, block, hdr_lo, hdr_hi;
-  int window, part, npar, units_in_block, npos;
+  int window, part, npar, units_in_block, npos, index_in_block;
 };
 __device__ __forceinline__ Desc decode(uint32_t dw) {
   Desc d;
@@ -307,7 +307,9 @@ __device__ __forceinline__ Desc decode(uint32_t dw) {
   d.units_in_block = (int)(w3 & 0xffffu);
   d.npos = (int)((w3 >> 16) & 0xffu);
   d.hdr_lo = (uint32_t)__builtin_amdgcn_readlane((int)dw, 4);
-  d.hdr_hi = (uint32_t)__builtin_amdgcn_readlane((int)dw, 5);
+  const uint32_t w5 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 5);
+  d.hdr_hi = w5 & 0xffffu;
+  d.index_in_block = (int)(w5 >> 16);
   return d;
 }
 
@@ -491,6 +493,12 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
         for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
       }
+      // the overflow sums, read in the same LDS round trip (unused overflow slots hold 0; slots
+      // beyond the cleared range are not read)
+      AT ovf[rsr::kMaxOverflow / 64];
+#pragma unroll
+      for (int c = 0; c < rsr::kMaxOverflow / 64; ++c)
+        ovf[c] = (c < D.npar) ? win[rsr::kOverflowBase + c * 64 + lane] : (AT)0;
       // vals[0..2]: the three levels inside the lane; vals[3..6]: lane bits 0..3 (value bits 3..6);
       // vals[7]: the lane's total, from which the two row-index bits (value bits 7, 8) and the
       // window total follow.
@@ -513,7 +521,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
         for (int c = 0; c < rsr::kMaxOverflow / 64; ++c) {
           if (c < D.npar) {
-            const AT val = win[rsr::kOverflowBase + c * 64 + lane];  // unused overflow slots hold 0
+            const AT val = ovf[c];
             const uint32_t pw = (c < 2) ? parw0 : parw1;
             const uint32_t par = (c & 1) ? (pw >> 16) : (pw & 0xffffu);
 #pragma unroll
@@ -555,7 +563,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
         // (the two halves of the wavefront take every other record, two records per step, so that
         // four LDS reads are in flight instead of one dependent pair)
         const int bit = lane & 15, q = (lane >> 4) & 1, half = lane >> 5;
-        const AT* base = rec + (size_t)(bu[slot] - u_begin) * rsr::kRecordWords;
+        const AT* base = rec + (size_t)((int)ix - D.index_in_block) * rsr::kRecordWords;  // the block's units are consecutive
         const int word = (bit < p.kw) ? bit : 9;
         auto term = [&](uint32_t meta, AT t) {
           const bool use = ((int)(meta >> 16) == q) && (bit < p.kw || (((meta & 0xffffu) >> (bit - p.kw)) & 1u));
@@ -575,10 +583,11 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
           const AT* ra = base + (size_t)j * rsr::kRecordWords;
           sum_a += term(__builtin_bit_cast(uint32_t, ra[10]), ra[word]);
         }
-        AT sum = sum_a + sum_b;
-        sum += __shfl_xor(sum, 32, 64);
-        const AT minus = __shfl(sum, lane + 16, 64);  // part 1 sits 16 lanes up
-        const AT res = sum - minus;                   // Proposition 2.1: v.B(1) - v.B(2)
+        // the two halves of the wavefront, then part 1 (second 16-lane row) from part 0: lane swaps
+        const Swapped hs = swap32(__builtin_bit_cast(uint32_t, sum_a + sum_b));
+        const AT sum = __builtin_bit_cast(AT, hs.x) + __builtin_bit_cast(AT, hs.y);
+        const Swapped ps = swap16(__builtin_bit_cast(uint32_t, sum));  // .x: row 0 (part 0), .y: row 1 (part 1)
+        const AT res = __builtin_bit_cast(AT, ps.x) - __builtin_bit_cast(AT, ps.y);  // Proposition 2.1: v.B(1) - v.B(2)
         // value bit `bit` belongs to column k-1-bit of the block (first column most significant)
         const int width = ((int)D.block == p.nblocks - 1) ? p.last_width : p.k;
         const int col = p.k - 1 - bit;

@@ -148,7 +148,7 @@ void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std:
   u.npos = (uint8_t)npos;
   u.ngroups = (uint8_t)ngroups;
   u.hdr_lo = (uint32_t)hdr;
-  u.hdr_hi = (uint32_t)(hdr >> 32);
+  u.hdr_hi = (uint16_t)(hdr >> 32);
   u.nidx = nidx;
   u.npieces = (uint32_t)count;
   const int full = npos / kGranulePositions;
@@ -440,6 +440,7 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
       Unit u = B.units[i];
       u.stream_off += (uint32_t)(pe * sizeof(uint16_t) / kStreamAlign);
       u.units_in_block = (uint16_t)B.units.size();
+      u.index_in_block = (uint16_t)i;
       P.units[pu + i] = u;
     }
     P.max_units_per_block = std::max<uint32_t>(P.max_units_per_block, (uint32_t)B.units.size());

@@ -196,7 +196,7 @@ def check_streams(h, S):
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
             assert U["block"] == b and U["part"] < info.parts
-            assert U["units_in_block"] == blk[b + 1] - blk[b]
+            assert U["units_in_block"] == blk[b + 1] - blk[b] and U["index_in_block"] == ui - blk[b]
             assert U["window"] < (1 << (k - kw))
             npos = int(U["npos"])
             assert npos % 2 == 0 and npos <= MAX_POS and int(U["npar"]) <= MAX_OVF // LANES
