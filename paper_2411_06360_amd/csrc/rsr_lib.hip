@@ -118,15 +118,6 @@ struct KArgs {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// The index stream is read once per product: non-temporal loads keep it from displacing the
-// small, reused data (descriptors, activations) in the caches.
-__device__ __forceinline__ u32x4 load_granule(const unsigned char* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
-}
-__device__ __forceinline__ uint32_t load_pair(const unsigned char* p) {
-  return __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
-}
-
 // ---- wavefront sums with DPP (no LDS traffic).  The total ends up in lane 63. ----
 template <int CTRL, int ROW_MASK, int BANK_MASK>
 __device__ __forceinline__ float dpp_get(float x) {
@@ -354,24 +345,29 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   // wait for the current unit never waits for the next one.
   uint32_t eA[NG][4], eB[NG][4];
   uint32_t tA[3], tB[3];  // positions behind the last full granule: up to three rows of dwords
-  auto issue_granule = [&](uint32_t stream_off, int npos, int gq, uint32_t (&e)[NG][4]) {
-    const unsigned char* us = stream + (size_t)stream_off * rsr::kStreamAlign;
-    const bool need = gq < (npos >> 3);
-    const unsigned char* src = need ? us + gq * 1024 : stream;
-    const u32x4 x = load_granule(src + (need ? lane16 : 0u));  // a load that is not needed: one address for all lanes
+  // A unit's stream is read through a buffer descriptor that covers exactly the unit: a load past
+  // its end (a granule or a dword row the unit does not have, or a unit that does not exist:
+  // npos = 0) returns zeros without touching memory, and an address costs no vector arithmetic.
+  auto unit_rsrc = [&](uint32_t stream_off, int npos) {
+    unsigned char* us = const_cast<unsigned char*>(stream) + (size_t)stream_off * rsr::kStreamAlign;
+    return __builtin_amdgcn_make_buffer_rsrc(us, 0, npos * rsr::kPositionBytes, 0x00020000);
+  };
+  constexpr int kNonTemporal = 2;  // the stream is read once per product: keep it from displacing reused data
+  // (the offsets go into the per-lane offset, which the range check covers; the scalar offset stays 0)
+  const uint32_t lane16_hi = lane16 + 4096u;
+  auto issue_granule = [&](__amdgpu_buffer_rsrc_t rs, int gq, uint32_t (&e)[NG][4]) {
+    const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(gq < 4 ? lane16 : lane16_hi) + (gq & 3) * 1024, 0, kNonTemporal);
     e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
   };
-  auto issue_pair = [&](uint32_t stream_off, int npos, int j, uint32_t (&et)[3]) {
-    const unsigned char* ut = stream + (size_t)stream_off * rsr::kStreamAlign + (size_t)(npos >> 3) * 1024;
-    const bool need = j < ((npos & 7) >> 1);
-    const unsigned char* src = need ? ut + j * 256 : stream;
-    et[j] = load_pair(src + (need ? lane4 : 0u));
+  auto issue_pair = [&](__amdgpu_buffer_rsrc_t rs, uint32_t pair_base, int j, uint32_t (&et)[3]) {
+    et[j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)pair_base + j * 256, 0, kNonTemporal);
   };
   auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
+    const __amdgpu_buffer_rsrc_t rs = unit_rsrc(stream_off, npos);
 #pragma unroll
-    for (int gq = 0; gq < NG; ++gq) issue_granule(stream_off, npos, gq, e);
+    for (int gq = 0; gq < NG; ++gq) issue_granule(rs, gq, e);
 #pragma unroll
-    for (int j = 0; j < 3; ++j) issue_pair(stream_off, npos, j, et);
+    for (int j = 0; j < 3; ++j) issue_pair(rs, lane4 + (uint32_t)(npos >> 3) * 1024u, j, et);
   };
 
   // The activation vector is staged first: its loads go out before anything else so that they do
@@ -398,9 +394,9 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       bu[tid] = blk_unit[blk < blk_end ? blk : blk_end];
     }
     if (tid < p.nslot) done[tid] = 0;
-    // the first two units of every wavefront are fixed (u_begin + wave, u_begin + wave + nwaves), so
-    // that their descriptors can be fetched before the barrier; later ones come from the counter
-    if (tid == 0) *ctr = 2u * (unsigned)nwaves;
+    // the first unit of every wavefront is fixed (u_begin + wave), so that its descriptor can be
+    // fetched before the barrier; later ones come from the counter
+    if (tid == 0) *ctr = (unsigned)nwaves;
     const uint32_t u_begin = blk_unit[rb0];
     if (first_round) {
       // vl[rows] = 0 serves the null row index.  (Written before the descriptor loads go out:
@@ -418,7 +414,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     }
     auto early_desc = [&](uint32_t u) { return unit_words[(size_t)(u < (uint32_t)p.nunits ? u : 0u) * 8 + (lane & 7)]; };
     const uint32_t dw = early_desc(u_begin + (uint32_t)wave);
-    uint32_t dw1 = early_desc(u_begin + (uint32_t)(wave + nwaves));
     Desc D = decode(dw);
     issue(D.stream_off, D.npos, eA, tA);
     __syncthreads();
@@ -432,8 +427,8 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     const int rb1 = rb0 + nblk;
     const uint32_t n_tot = bu[nblk] - u_begin;  // units of this round, numbered 0 .. n_tot-1
 
-    // unit index pipeline: ix is summed now, ix1 is the one whose stream is loaded meanwhile, and
-    // the descriptor of ix2 is fetched; units come from the workgroup's counter
+    // A wavefront reserves its next unit only when it starts on the current one (not earlier): the
+    // last units of the round then go to the wavefronts that get there first.
     auto take = [&]() {
       unsigned t = 0;
       if (lane == 0) t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
@@ -443,16 +438,14 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       return unit_words[(size_t)(ixq < n_tot ? u_begin + ixq : 0u) * 8 + (lane & 7)];
     };
     uint32_t ix = (uint32_t)wave;
-    uint32_t ix1 = (uint32_t)(wave + nwaves);
 
-    // One unit from buffer (e, et); the next unit's stream goes into (en, etn) first.
+    // One unit from buffer (e, et); the next unit's stream goes into (en, etn) meanwhile.
     auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[3], uint32_t (&en)[NG][4], uint32_t (&etn)[3]) {
-      const uint32_t ix2 = (ix1 < n_tot) ? take() : n_tot;
-      const uint32_t dw2 = fetch_desc(ix2);
-      Desc D1 = decode(dw1);
-      if (ix1 >= n_tot) D1.npos = 0;
-      // (its loads go out one by one between the steps below: a wavefront that issues a whole
-      // unit at once waits for room in the memory pipeline while it could be summing)
+      const uint32_t ix1 = take();
+      const uint32_t dw1 = fetch_desc(ix1);
+      // (the next unit's descriptor arrives during the first granules; its loads go out one by one
+      // between the later steps: a wavefront that issues a whole unit at once waits for room in
+      // the memory pipeline while it could be summing)
 
       // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
@@ -463,13 +456,23 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       AT a = (AT)0;
       uint32_t sa = winbase + (uint32_t)(rsr::kWindow + (lane & (rsr::kDummySlots - 1))) * 4u;  // nothing to deliver yet
       const int full = D.npos >> 3;
-#pragma unroll
-      for (int gq = 0; gq < NG; ++gq) {
+      auto step = [&](int gq) {
         if (gq < full) {
           const uint32_t hb = ((gq < 4 ? D.hdr_lo : D.hdr_hi) >> (8 * (gq & 3))) & 0xffu;
           granule_step(hb, e[gq][0], e[gq][1], e[gq][2], e[gq][3], a, sa, winbase, vl);
         }
-        issue_granule(D1.stream_off, D1.npos, gq, en);
+      };
+#pragma unroll
+      for (int gq = 0; gq < NG / 2; ++gq) step(gq);
+      Desc D1 = decode(dw1);
+      if (ix1 >= n_tot) D1.npos = 0;
+      const __amdgpu_buffer_rsrc_t rs1 = unit_rsrc(D1.stream_off, D1.npos);
+      const uint32_t pair_base1 = lane4 + (uint32_t)(D1.npos >> 3) * 1024u;
+#pragma unroll
+      for (int gq = NG / 2; gq < NG; ++gq) {
+        step(gq);
+        issue_granule(rs1, 2 * (gq - NG / 2), en);
+        issue_granule(rs1, 2 * (gq - NG / 2) + 1, en);
       }
       {
         const int pairs = (D.npos & 7) >> 1;
@@ -478,7 +481,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
         for (int j = 0; j < 3; ++j) {
           if (j < pairs) pair_step((tm >> (2 * j)) & 3u, et[j], a, sa, winbase, vl);
-          issue_pair(D1.stream_off, D1.npos, j, etn);
+          issue_pair(rs1, pair_base1, j, etn);
         }
       }
       *reinterpret_cast<AT*>(lds + sa) = a;  // the last group
@@ -594,7 +597,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
         if (lane < 16 && bit < p.k && col < width) outp[(int64_t)D.block * p.k + col] = res;
       }
       ix = ix1; D = D1;
-      ix1 = ix2; dw1 = dw2;
     };
 
     while (ix < n_tot) {
@@ -683,7 +685,6 @@ int upload(rsr_handle* h, const rsr::Packed& P) {
   h->stream_bytes = P.stream.size() * sizeof(uint16_t);
   h->unit_bytes = P.units.size() * sizeof(rsr::Unit);
   h->blk_bytes = P.blk_unit.size() * sizeof(uint32_t);
-  // The first KB of the stream is what the loads a unit does not need read: it has to exist.
   RSR_HIP_TRY(hipMalloc(&h->d_stream, h->stream_bytes + 1024));
   RSR_HIP_TRY(hipMalloc(&h->d_units, h->unit_bytes + 32));
   RSR_HIP_TRY(hipMalloc(&h->d_blk_unit, h->blk_bytes + 16));
