@@ -188,6 +188,21 @@ __device__ __forceinline__ Swapped swap16(uint32_t v) {  // .x: rows 0,0,2,2 of 
   return r;
 }
 
+// counter += 1 on behalf of the wavefront; returns the old value (wavefront-uniform).  One lane
+// does it, with the execution mask set by hand: the compiler's own version of "lane 0 only" costs
+// a dozen instructions.  LDS operations of a wavefront execute in order, so stores issued before
+// this are in place before the counter moves.
+__device__ __forceinline__ uint32_t lds_count_up(uint32_t lds_byte_addr) {
+  uint32_t old;
+  uint64_t saved;
+  asm volatile(
+      "s_mov_b64 %[sv], exec\n s_mov_b64 exec, 1\n ds_add_rtn_u32 %[o], %[ad], %[one]\n s_mov_b64 exec, %[sv]\n s_waitcnt lgkmcnt(0)\n"
+      : [o] "=&v"(old), [sv] "=&s"(saved)
+      : [ad] "v"(lds_byte_addr), [one] "v"(1u)
+      : "memory");
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)old);
+}
+
 template <typename VT> struct Acc;
 template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
@@ -385,6 +400,11 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     if (i < n16) sv[j] = v16[i];
   }
 
+  const __amdgpu_buffer_rsrc_t units_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(unit_words), 0, p.nunits * 32, 0x00020000);
+  const uint32_t desc_lane = (uint32_t)(lane & 7) * 4u;
+  // where a lane puts its part of a unit record (see below), in bytes from the record's start
+  const uint32_t rec_lane = 4u * (lane < 7 ? (uint32_t)lane : lane == 7 ? 9u : lane == 15 ? 7u : lane == 23 ? 8u : lane == 31 ? 10u : 12u);
   bool first_round = true;
   for (int rb0 = blk_begin; rb0 < blk_end;) {
     // ---- round set-up.  A round covers as many consecutive blocks as there are completion
@@ -429,13 +449,9 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 
     // A wavefront reserves its next unit only when it starts on the current one (not earlier): the
     // last units of the round then go to the wavefronts that get there first.
-    auto take = [&]() {
-      unsigned t = 0;
-      if (lane == 0) t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-      return (uint32_t)__builtin_amdgcn_readfirstlane(t);
-    };
+    auto take = [&]() { return lds_count_up(p.off_ctr); };
     auto fetch_desc = [&](uint32_t ixq) {  // always one load; past the end it reads unit 0 (unused)
-      return unit_words[(size_t)(ixq < n_tot ? u_begin + ixq : 0u) * 8 + (lane & 7)];
+      return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(units_rsrc, (int)desc_lane, (int)((ixq < n_tot ? u_begin + ixq : 0u) * 32u), 0);
     };
     uint32_t ix = (uint32_t)wave;
 
@@ -449,9 +465,12 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 
       // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
+        // the window and the overflow slots in use (nobody reads the dummies)
         uint4* w16 = reinterpret_cast<uint4*>(win);
-        const int n16w = (rsr::kOverflowBase + 64 * D.npar) / 4;  // the window, the dummies, the overflow slots in use
-        for (int i = lane; i < n16w; i += 64) w16[i] = make_uint4(0, 0, 0, 0);
+        w16[lane] = make_uint4(0, 0, 0, 0);
+        w16[lane + 64] = make_uint4(0, 0, 0, 0);
+        static_assert(rsr::kWindow == 512 && rsr::kOverflowBase % 4 == 0 && rsr::kMaxOverflow <= 256, "zeroing below");
+        if (lane < 16 * D.npar) w16[rsr::kOverflowBase / 4 + lane] = make_uint4(0, 0, 0, 0);
       }
       AT a = (AT)0;
       uint32_t sa = winbase + (uint32_t)(rsr::kWindow + (lane & (rsr::kDummySlots - 1))) * 4u;  // nothing to deliver yet
@@ -527,8 +546,12 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
             const AT val = ovf[c];
             const uint32_t pw = (c < 2) ? parw0 : parw1;
             const uint32_t par = (c & 1) ? (pw >> 16) : (pw & 0xffffu);
+            const uint32_t vbits = __builtin_bit_cast(uint32_t, val);
 #pragma unroll
-            for (int beta = 0; beta < 7; ++beta) vals[beta] += ((par >> beta) & 1) ? val : (AT)0;
+            for (int beta = 0; beta < 7; ++beta) {  // val where the bit is set, +0 elsewhere
+              const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)par, beta, 1);
+              vals[beta] += __builtin_bit_cast(AT, vbits & m);
+            }
             vals[7] += val;
           }
         }
@@ -544,19 +567,17 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       const AT bit7 = __builtin_bit_cast(AT, t16.y);
       const AT bit8 = __builtin_bit_cast(AT, b16.x) + __builtin_bit_cast(AT, b16.y);
       // ---- record, and completion of the block: lanes 0..7 finish the sums ----
+      // One store writes the record: lanes 0..6 hold the sums of value bits 0..6, lane 7 the
+      // window's total, lane 15 (second row) bit 7, lane 23 bit 8; lane 31 adds part and window.
       const int slot = (int)D.block - rb0;
-      unsigned before = 0;
-      if (lane < 8) {
-        AT* rr = rec + (size_t)ix * rsr::kRecordWords;
-        rr[lane == 7 ? 9 : lane] = total;
-        if (lane == 7) {
-          rr[7] = bit7;  // lane bit 4 = rows 1 and 3 = value bit 7
-          rr[8] = bit8;  // lane bit 5 = rows 2 and 3 = value bit 8
-          rr[10] = __builtin_bit_cast(AT, (uint32_t)((D.part << 16) | D.window));
-          before = __hip_atomic_fetch_add(&done[slot], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
-        }
+      {
+        AT val = total;
+        val = (lane == 15) ? bit7 : val;  // lane bit 4 = rows 1 and 3 = value bit 7
+        val = (lane == 23) ? bit8 : val;  // lane bit 5 = rows 2 and 3 = value bit 8
+        val = (lane == 31) ? __builtin_bit_cast(AT, (uint32_t)((D.part << 16) | D.window)) : val;
+        *reinterpret_cast<AT*>(lds + p.off_rec + ix * (rsr::kRecordWords * 4) + rec_lane) = val;
       }
-      before = read_lane<unsigned>(before, 7);
+      const unsigned before = lds_count_up(p.off_done + (uint32_t)slot * 4u);
       if ((int)before + 1 == D.units_in_block) {
         // ---- last unit of the block: remaining fold levels, ternary combine, store ----
         // Lane (bit + 16 * part) adds up, over the block's units, "sum of u[j] over the values j
