@@ -6,10 +6,12 @@
 //     index streams.  Column blocks are independent (the paper's parallelisation I, Appendix C.1).
 //   * Its wavefronts take work units (one window of 2^kw row values of one block and part, see
 //     rsr_format.h) from an LDS counter.  For a unit a wavefront
-//       1. streams the unit's diagonals with 16-byte loads and gathers v[sigma(p)] from LDS into
-//          8 accumulators per lane - the segmented sums of Eq. SS2, one accumulator per segment;
-//       2. drops the sums into its private window of u in LDS (plain stores: every slot has one
-//          writer), and reads the window back in value order;
+//       1. reads the unit's stream with 16-byte buffer loads (the next unit's loads go out while
+//          the current one is summed) and walks its positions: at an index position every lane
+//          gathers v[sigma(p)] from LDS into its running sum - the segmented sums of Eq. SS2, one
+//          piece of a segment per lane - and at a header position drops the sum into the slot of
+//          its private window of u in LDS (plain stores: every slot has one writer);
+//       2. reads the window back in value order;
 //       3. takes the low kw levels of the RSR++ fold (Section 4.3, Algorithm 3): "sum the
 //          odd-indexed entries, then add neighbours" - three levels inside a lane's 8 consecutive
 //          values, the next six across the 64 lanes - and leaves kw sums plus the window total
@@ -207,7 +209,7 @@ template <typename VT> struct Acc;
 template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
 
-// ---- the stream positions of a lane unit, eight (one granule) or two (one dword) at a time ----
+// ---- the stream positions of a unit, eight (one granule) or two (one dword) at a time ----
 // Per position and lane the stream holds a uint16 x.  At a header position (bit set in `hb`) the
 // running sum `a` of the group that ends here goes to the window slot the lane was given at the
 // group's own header (LDS byte address `sa`), x names the next slot and the sum restarts; at any
