@@ -299,23 +299,27 @@ __device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, 
       : "scc", "memory");
 }
 
-// The scalar fields of a unit descriptor (wavefront-uniform); its 8 dwords sit in lanes 0..7 of dw.
+// The scalar fields of a unit descriptor.  The unit number is wavefront-uniform, so the descriptor is
+// read with scalar loads: these do not queue with the vector loads of the compute unit, which
+// return in the order they were issued across all its wavefronts - a descriptor that has to come
+// from memory would hold back everything requested after it (the other wavefronts' share of the
+// activation vector at the start, stream data later).
 struct Desc {
   uint32_t stream_off, block, hdr_lo, hdr_hi;
   int window, part, npar, units_in_block, npos, index_in_block;
 };
-__device__ __forceinline__ Desc decode(uint32_t dw) {
+__device__ __forceinline__ Desc load_desc(const uint32_t* __restrict__ unit_words, uint32_t u) {
+  const uint32_t* w = unit_words + (size_t)__builtin_amdgcn_readfirstlane((int)u) * 8;
   Desc d;
-  d.stream_off = (uint32_t)__builtin_amdgcn_readlane((int)dw, 0);
-  d.block = (uint32_t)__builtin_amdgcn_readlane((int)dw, 1);
-  const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 2), w3 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 3);
+  d.stream_off = w[0];
+  d.block = w[1];
+  const uint32_t w2 = w[2], w3 = w[3], w5 = w[5];
   d.window = (int)(w2 & 0xffffu);
   d.part = (int)((w2 >> 16) & 0xffu);
   d.npar = (int)(w2 >> 24);
   d.units_in_block = (int)(w3 & 0xffffu);
   d.npos = (int)((w3 >> 16) & 0xffu);
-  d.hdr_lo = (uint32_t)__builtin_amdgcn_readlane((int)dw, 4);
-  const uint32_t w5 = (uint32_t)__builtin_amdgcn_readlane((int)dw, 5);
+  d.hdr_lo = w[4];
   d.hdr_hi = w5 & 0xffffu;
   d.index_in_block = (int)(w5 >> 16);
   return d;
@@ -402,27 +406,35 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     if (i < n16) sv[j] = v16[i];
   }
 
-  const __amdgpu_buffer_rsrc_t units_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(unit_words), 0, p.nunits * 32, 0x00020000);
-  const uint32_t desc_lane = (uint32_t)(lane & 7) * 4u;
   // where a lane puts its part of a unit record (see below), in bytes from the record's start
   const uint32_t rec_lane = 4u * (lane < 7 ? (uint32_t)lane : lane == 7 ? 9u : lane == 15 ? 7u : lane == 23 ? 8u : lane == 31 ? 10u : 12u);
   bool first_round = true;
   for (int rb0 = blk_begin; rb0 < blk_end;) {
     // ---- round set-up.  A round covers as many consecutive blocks as there are completion
     //      counters (nslot <= 64) and unit records (ucap). ----
-    if (tid <= p.nslot) {
-      const int blk = rb0 + tid;
-      bu[tid] = blk_unit[blk < blk_end ? blk : blk_end];
+    // Usually all blocks of the workgroup fit in one round; otherwise the block table of the next
+    // nslot blocks is fetched to find out how many do.  (By the last threads of the workgroup:
+    // vector loads return in the order of issue across the wavefronts of a compute unit.)
+    const uint32_t u_begin = blk_unit[rb0];
+    const uint32_t u_last = blk_unit[blk_end];
+    const bool one_round = (blk_end - rb0 <= p.nslot) && (u_last - u_begin <= (uint32_t)p.ucap);
+    if (!one_round) {
+      for (int i = (int)blockDim.x - 1 - tid; i <= p.nslot; i += (int)blockDim.x) {
+        const int blk = rb0 + i;
+        bu[i] = blk_unit[blk < blk_end ? blk : blk_end];
+      }
     }
     if (tid < p.nslot) done[tid] = 0;
     // the first unit of every wavefront is fixed (u_begin + wave), so that its descriptor can be
     // fetched before the barrier; later ones come from the counter
     if (tid == 0) *ctr = (unsigned)nwaves;
-    const uint32_t u_begin = blk_unit[rb0];
+    // The first stream loads go out before anything waits for the activation vector: they are
+    // behind it in the queue anyway.
+    const uint32_t u_first = u_begin + (uint32_t)wave;
+    Desc D = load_desc(unit_words, u_first < (uint32_t)p.nunits ? u_first : 0u);
+    issue(D.stream_off, D.npos, eA, tA);
     if (first_round) {
-      // vl[rows] = 0 serves the null row index.  (Written before the descriptor loads go out:
-      // loads return in order, so nothing here waits for those.)
+      // vl[rows] = 0 serves the null row index.
       uint4* l16 = reinterpret_cast<uint4*>(vl);
 #pragma unroll
       for (int j = 0; j < kEarly; ++j) {
@@ -434,33 +446,29 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       if (tid == 0) vl[p.rows] = (VT)0;
       first_round = false;
     }
-    auto early_desc = [&](uint32_t u) { return unit_words[(size_t)(u < (uint32_t)p.nunits ? u : 0u) * 8 + (lane & 7)]; };
-    const uint32_t dw = early_desc(u_begin + (uint32_t)wave);
-    Desc D = decode(dw);
-    issue(D.stream_off, D.npos, eA, tA);
     __syncthreads();
-    int nblk;
-    {
+    int nblk = blk_end - rb0;
+    if (!one_round) {
       const bool ok = (lane < p.nslot) && (rb0 + lane < blk_end) && (bu[lane + 1] - u_begin <= (uint32_t)p.ucap);
       const uint64_t mask = __ballot(ok);
       nblk = (~mask == 0) ? 64 : __builtin_ctzll(~mask);
       if (nblk < 1) nblk = 1;  // a single block always fits: ucap >= the largest block
     }
     const int rb1 = rb0 + nblk;
-    const uint32_t n_tot = bu[nblk] - u_begin;  // units of this round, numbered 0 .. n_tot-1
+    const uint32_t n_tot = (one_round ? u_last : bu[nblk]) - u_begin;  // units of this round, numbered 0 .. n_tot-1
 
     // A wavefront reserves its next unit only when it starts on the current one (not earlier): the
     // last units of the round then go to the wavefronts that get there first.
     auto take = [&]() { return lds_count_up(p.off_ctr); };
-    auto fetch_desc = [&](uint32_t ixq) {  // always one load; past the end it reads unit 0 (unused)
-      return (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(units_rsrc, (int)desc_lane, (int)((ixq < n_tot ? u_begin + ixq : 0u) * 32u), 0);
+    auto fetch_desc = [&](uint32_t ixq) {  // past the end it reads unit 0 (unused)
+      return load_desc(unit_words, ixq < n_tot ? u_begin + ixq : 0u);
     };
     uint32_t ix = (uint32_t)wave;
 
     // One unit from buffer (e, et); the next unit's stream goes into (en, etn) meanwhile.
     auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[3], uint32_t (&en)[NG][4], uint32_t (&etn)[3]) {
       const uint32_t ix1 = take();
-      const uint32_t dw1 = fetch_desc(ix1);
+      Desc D1 = fetch_desc(ix1);
       // (the next unit's descriptor arrives during the first granules; its loads go out one by one
       // between the later steps: a wavefront that issues a whole unit at once waits for room in
       // the memory pipeline while it could be summing)
@@ -485,7 +493,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       };
 #pragma unroll
       for (int gq = 0; gq < NG / 2; ++gq) step(gq);
-      Desc D1 = decode(dw1);
       if (ix1 >= n_tot) D1.npos = 0;
       const __amdgpu_buffer_rsrc_t rs1 = unit_rsrc(D1.stream_off, D1.npos);
       const uint32_t pair_base1 = lane4 + (uint32_t)(D1.npos >> 3) * 1024u;
