@@ -30,8 +30,10 @@
 //     slot 64c + x).  Then the groups follow: a header position and n index positions (n = the
 //     group's longest piece).  The header names, per lane, the window slot that receives the
 //     lane's sum for the group; lanes without a piece name a dummy slot.  An index position holds
-//     the next row of each lane's piece, or the null row index `rows` (which reads a zero kept
-//     behind the activation vector in LDS) once the piece is exhausted.  A bit mask in the
+//     one row of each lane's piece, or the null row index `rows` (which reads a zero kept behind
+//     the activation vector in LDS): a piece shorter than its group leaves some positions of its
+//     lane empty, and which ones is the packer's choice (it places the rows so that the lanes of
+//     a half wavefront read different LDS banks where possible).  A bit mask in the
 //     descriptor marks the header positions.  The number of positions is even (a null position is
 //     appended if needed) and at most kMaxPositions.
 //   * In memory a lane's uint16s of 8 consecutive positions are adjacent: positions 8g .. 8g+7

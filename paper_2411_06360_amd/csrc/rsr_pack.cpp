@@ -39,32 +39,154 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Longest piece: its group (header + rows) and all parent positions have to fit into one unit.
 constexpr int kMaxPieceRows = kMaxPositions - 1 - kMaxOverflow / kLanes;
 
-// Bipartite matching (augmenting paths) of the lanes l0 .. l0+31 to the 32 LDS banks: a lane can
-// take a bank if one of the rows it has left lies in it.
-struct BankMatch {
-  const uint16_t (*rows_of)[kMaxPieceRows];
-  const uint32_t* left;
-  int l0;
-  int bank_lane[32];   // lane matched to the bank, or -1
-  int lane_pick[32];   // index into rows_of[lane] of the matched row, or -1
-  bool seen_bank[32];
-  bool augment(int lane) {
-    for (uint32_t c = 0; c < left[lane]; ++c) {
-      const int bank = rows_of[lane][c] & 31;
-      if (seen_bank[bank]) continue;
-      seen_bank[bank] = true;
-      if (bank_lane[bank] < 0 || augment(bank_lane[bank])) {
-        bank_lane[bank] = lane;
-        lane_pick[lane - l0] = (int)c;
-        return true;
-      }
-    }
-    return false;
-  }
+// ---- LDS banks ----
+// A gather instruction reads one activation per lane; the LDS serves the 32 lanes of a half
+// wavefront together and takes one pass per distinct address in the fullest bank (bank of a
+// float activation = row mod 32).  Two things are free in the layout and are used to bring every
+// position as close to one pass as possible:
+//   * which pieces share a half wavefront: pieces of equal length may trade places anywhere in
+//     the unit, any two pieces may trade places inside their group.  A randomised search moves
+//     pieces until no bank has more rows in a half group than the group has positions (or the
+//     iteration budget is spent);
+//   * at which of the group's positions a lane reads which of its rows (a piece is a sum).  This is
+//     an edge colouring of the bipartite multigraph lanes x banks (an edge per row, a colour per
+//     position): with at most n rows per lane and per bank, n colours suffice (Koenig), i.e. every
+//     position is conflict-free.  Rows of a bank beyond n are placed afterwards where they cost
+//     the fewest extra passes.
+constexpr int kBanks = 32;
+constexpr int kHalf = 32;
+
+struct HalfGroup {
+  int n = 0;                 // positions of the group
+  uint16_t deg[kBanks];      // rows per bank
 };
 
-// One unit: pcs[first .. first+count) (sorted by descending length, count a multiple of 64 except
-// in the last unit of a window), their slots, and the parents of the overflow slots among them.
+inline int half_cost(const HalfGroup& h) {
+  int mx = h.n, sq = 0;
+  for (int b = 0; b < kBanks; ++b) {
+    const int d = h.deg[b];
+    if (d > mx) mx = d;
+    const int e = d - h.n;
+    if (e > 0) sq += 8 * e * e;
+    if (e + 1 > 0) sq += (e + 1) * (e + 1);
+  }
+  return 1024 * mx + sq;
+}
+
+// Edge colouring of one half group.  row_of[l][0 .. len[l]) are the rows of lane l; on return
+// place[l][t] is the row lane l reads at position t (or `null_index`).
+//
+// A bank with more than n rows cannot be conflict-free.  Its rows beyond the n-th go to a second
+// (third, fourth) copy of the bank; the graph lanes x bank copies still has at most n edges per
+// node, so it has a proper colouring, in which a position sees every copy at most once: a
+// position costs as many passes as it uses copies of its fullest bank.  The rows of the extra
+// copies are coloured first and take the lowest colour that is free, which gathers them in few
+// positions.  (Rows beyond the fourth copy are placed afterwards wherever their lane is free.)
+constexpr int kBankCopies = 4;
+
+void colour_half(int n, const uint16_t (*row_of)[kMaxPieceRows], const int* len, uint16_t null_index,
+                 uint16_t (*place)[kMaxPieceRows]) {
+  constexpr int kNodes = kBanks * kBankCopies;
+  int16_t at_lane[kHalf][kMaxPieceRows], at_bank[kNodes][kMaxPieceRows];  // edge at (node, colour) or -1
+  for (int l = 0; l < kHalf; ++l)
+    for (int c = 0; c < n; ++c) { at_lane[l][c] = -1; place[l][c] = null_index; }
+  for (int v = 0; v < kNodes; ++v)
+    for (int c = 0; c < n; ++c) at_bank[v][c] = -1;
+  struct Edge { uint8_t lane, node; int8_t colour; uint16_t row; };
+  Edge edges[kHalf * kMaxPieceRows];
+  int ne = 0;
+  int bank_count[kBanks] = {0};
+  int16_t todo[kHalf * kMaxPieceRows];  // edges in the order they are coloured
+  int n_extra = 0, n_todo = 0;
+  int16_t late[kHalf * kMaxPieceRows];
+  int n_late = 0;
+  // Lanes with the most rows first: the rows that find their bank full, and go to its extra copies,
+  // then belong to the lanes with the most room.
+  int order[kHalf];
+  for (int l = 0; l < kHalf; ++l) order[l] = l;
+  std::stable_sort(order, order + kHalf, [&](int x, int y) { return len[x] > len[y]; });
+  for (int o = 0; o < kHalf; ++o) {
+    const int l = order[o];
+    for (int t = 0; t < len[l]; ++t) {
+      Edge& e = edges[ne];
+      e.lane = (uint8_t)l; e.row = row_of[l][t]; e.colour = -1;
+      const int bank = e.row & (kBanks - 1);
+      const int copy = bank_count[bank]++ / n;
+      e.node = (uint8_t)(bank + kBanks * (copy < kBankCopies ? copy : 0));
+      if (copy >= kBankCopies) {
+        late[n_late++] = (int16_t)ne;
+      } else if (copy > 0) {  // coloured before the others
+        for (int j = n_todo; j > n_extra; --j) todo[j] = todo[j - 1];
+        todo[n_extra++] = (int16_t)ne;
+        ++n_todo;
+      } else {
+        todo[n_todo++] = (int16_t)ne;
+      }
+      ++ne;
+    }
+  }
+  for (int q = 0; q < n_todo; ++q) {
+    const int i = todo[q];
+    Edge& e = edges[i];
+    const int u = e.lane, v = e.node;
+    int a = 0, b = 0;
+    if (q < n_extra) {
+      while (at_lane[u][a] >= 0 || at_bank[v][a] >= 0) { if (++a == n) break; }  // lowest colour free at both ends
+      if (a < n) { e.colour = (int8_t)a; at_lane[u][a] = (int16_t)i; at_bank[v][a] = (int16_t)i; continue; }
+      a = 0;
+    }
+    // (the other rows take the highest free colours, so that the swaps below rarely touch the low
+    // colours where the extra copies sit)
+    a = n - 1; b = n - 1;
+    while (at_lane[u][a] >= 0) --a;  // a colour the lane has not used (it has at most n rows)
+    while (at_bank[v][b] >= 0) --b;  // a colour the bank copy has not used (it has at most n rows)
+    if (at_bank[v][a] >= 0) {
+      // make `a` free at the bank copy: swap a and b along the path that starts there with colour a
+      int16_t path[2 * kHalf + kNodes + 2];
+      int np = 0, node = v, col = a;
+      bool at_bank_side = true;
+      for (;;) {
+        const int ei = at_bank_side ? at_bank[node][col] : at_lane[node][col];
+        if (ei < 0) break;
+        path[np++] = (int16_t)ei;
+        node = at_bank_side ? edges[ei].lane : edges[ei].node;
+        at_bank_side = !at_bank_side;
+        col = (col == a) ? b : a;
+      }
+      for (int j = 0; j < np; ++j) {
+        Edge& f = edges[path[j]];
+        at_lane[f.lane][f.colour] = -1; at_bank[f.node][f.colour] = -1;
+      }
+      for (int j = 0; j < np; ++j) {
+        Edge& f = edges[path[j]];
+        f.colour = (int8_t)(f.colour == a ? b : a);
+        at_lane[f.lane][f.colour] = path[j]; at_bank[f.node][f.colour] = path[j];
+      }
+    }
+    e.colour = (int8_t)a;
+    at_lane[u][a] = (int16_t)i; at_bank[v][a] = (int16_t)i;
+  }
+  // rows beyond the last copy: a free position of the lane where the bank is used least
+  if (n_late > 0) {
+    uint8_t mult[kMaxPieceRows][kBanks];
+    std::memset(mult, 0, sizeof(mult));
+    for (int i = 0; i < ne; ++i) if (edges[i].colour >= 0) ++mult[edges[i].colour][edges[i].node & (kBanks - 1)];
+    for (int j = 0; j < n_late; ++j) {
+      Edge& e = edges[late[j]];
+      const int bank = e.node & (kBanks - 1);
+      int best = -1;
+      for (int c = 0; c < n; ++c)
+        if (at_lane[e.lane][c] < 0 && (best < 0 || mult[c][bank] < mult[best][bank])) best = c;
+      e.colour = (int8_t)best;  // the lane has at most n rows, so a position is free
+      at_lane[e.lane][best] = late[j];
+      ++mult[best][bank];
+    }
+  }
+  for (int i = 0; i < ne; ++i) place[edges[i].lane][edges[i].colour] = edges[i].row;
+}
+
+// One unit: pcs[0 .. count) (sorted by descending length), their slots, and the parents of the
+// overflow slots among them.
 void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std::vector<uint16_t>& parents,
                const std::vector<uint16_t>& sigma, uint32_t block, uint32_t window, int part, uint16_t null_index,
                std::vector<uint16_t>& positions, BlockOut* out) {
@@ -79,61 +201,101 @@ void emit_unit(const Piece* pcs, const uint16_t* slot_ids, int count, const std:
     uint16_t* q = add_position(null_index);
     for (int l = 0; l < kLanes && c * kLanes + l < nov; ++l) q[l] = parents[(size_t)c * kLanes + l];
   }
+
+  // ---- which piece sits where: place i = (group i / 64, lane i % 64) holds piece at_place[i] ----
+  const int G = ceil_div(count, kLanes);
+  std::vector<int> at_place((size_t)G * kLanes);
+  for (int i = 0; i < G * kLanes; ++i) at_place[i] = i < count ? i : -1;
+  std::vector<HalfGroup> hg((size_t)G * 2);
+  auto bank_of = [&](int piece, int t) { return (int)(sigma[pcs[piece].start + t] & (kBanks - 1)); };
+  auto plen = [&](int piece) { return piece < 0 ? 0 : (int)pcs[piece].len; };
+  for (int g = 0; g < G; ++g)
+    for (int h = 0; h < 2; ++h) {
+      HalfGroup& x = hg[(size_t)g * 2 + h];
+      x.n = pcs[(size_t)g * kLanes].len;
+      std::memset(x.deg, 0, sizeof(x.deg));
+      for (int l = 0; l < kHalf; ++l) {
+        const int pc = at_place[(size_t)g * kLanes + h * kHalf + l];
+        for (int t = 0; t < plen(pc); ++t) ++x.deg[bank_of(pc, t)];
+      }
+    }
+  {
+    uint64_t rng = 0x9E3779B97F4A7C15ull ^ ((uint64_t)block << 24) ^ ((uint64_t)window << 8) ^ (uint64_t)part ^ ((uint64_t)count << 44);
+    auto next = [&]() { rng ^= rng << 13; rng ^= rng >> 7; rng ^= rng << 17; return (uint32_t)(rng >> 32); };
+    const int nplaces = G * kLanes;
+    auto overfull = [&](const HalfGroup& x) {
+      for (int b = 0; b < kBanks; ++b) if (x.deg[b] > x.n) return true;
+      return false;
+    };
+    int bad = 0;
+    for (const HalfGroup& x : hg) bad += overfull(x);
+    const int budget = 3000;
+    for (int it = 0; it < budget && bad > 0 && nplaces > kHalf; ++it) {
+      // a place in an overfull half group whose piece has a row in that half group's fullest bank
+      int i = (int)(next() % (uint32_t)nplaces);
+      {
+        int tries = 0;
+        while (tries < 8 && !overfull(hg[(size_t)(i / kLanes) * 2 + (i % kLanes) / kHalf])) { i = (int)(next() % (uint32_t)nplaces); ++tries; }
+      }
+      const int gi = i / kLanes, hi = (i % kLanes) / kHalf;
+      HalfGroup& X = hg[(size_t)gi * 2 + hi];
+      int worst = 0;
+      for (int b = 1; b < kBanks; ++b) if (X.deg[b] > X.deg[worst]) worst = b;
+      {
+        const int base = gi * kLanes + hi * kHalf, l0 = (int)(next() % kHalf);
+        for (int d = 0; d < kHalf; ++d) {
+          const int cand = base + (l0 + d) % kHalf, pc = at_place[cand];
+          bool has = false;
+          for (int t = 0; t < plen(pc); ++t) if (bank_of(pc, t) == worst) { has = true; break; }
+          if (has) { i = cand; break; }
+        }
+      }
+      const int j = (int)(next() % (uint32_t)nplaces);
+      const int gj = j / kLanes, hj = (j % kLanes) / kHalf;
+      if (gi == gj && hi == hj) continue;
+      const int pi = at_place[i], pj = at_place[j];
+      if (gi != gj && plen(pi) != plen(pj)) continue;  // every group keeps its lengths
+      HalfGroup& Y = hg[(size_t)gj * 2 + hj];
+      const int before = half_cost(X) + half_cost(Y);
+      const bool bad_x = overfull(X), bad_y = overfull(Y);
+      for (int t = 0; t < plen(pi); ++t) { const int b = bank_of(pi, t); --X.deg[b]; ++Y.deg[b]; }
+      for (int t = 0; t < plen(pj); ++t) { const int b = bank_of(pj, t); --Y.deg[b]; ++X.deg[b]; }
+      const int after = half_cost(X) + half_cost(Y);
+      if (after < before || (after == before && (next() & 3) == 0)) {
+        at_place[i] = pj; at_place[j] = pi;
+        bad += (int)overfull(X) + (int)overfull(Y) - (int)bad_x - (int)bad_y;
+      } else {
+        for (int t = 0; t < plen(pi); ++t) { const int b = bank_of(pi, t); ++X.deg[b]; --Y.deg[b]; }
+        for (int t = 0; t < plen(pj); ++t) { const int b = bank_of(pj, t); ++Y.deg[b]; --X.deg[b]; }
+      }
+    }
+  }
+
   uint64_t hdr = 0;
   int ngroups = 0;
   uint32_t nidx = 0;
-  for (int r0 = 0; r0 < count; r0 += kLanes) {
-    const int n = pcs[r0].len;  // the group's longest piece
-    const int cnt = std::min(kLanes, count - r0);
+  for (int g = 0; g < G; ++g) {
+    const int n = pcs[(size_t)g * kLanes].len;  // the group's longest piece
     hdr |= 1ull << npos;
     uint16_t* h = add_position(0);
-    for (int l = 0; l < kLanes; ++l) h[l] = (l < cnt) ? slot_ids[r0 + l] : (uint16_t)(kWindow + (l & (kDummySlots - 1)));
-    // The order of the rows inside a piece is free (they are summed).  It is chosen so that the 32
-    // lanes of each half of the wavefront, which the LDS serves together, read 32 different banks
-    // where possible (bank of a float activation = row mod 32): position after position, a maximum
-    // matching of lanes to banks over the rows each lane has left; a lane that stays unmatched takes
-    // the row whose bank is least used.
-    uint32_t left[kLanes];  // rows of the lane's piece not placed yet: rows_of[l][0 .. left)
-    uint16_t rows_of[kLanes][kMaxPieceRows];
-    for (int l = 0; l < cnt; ++l) {
-      left[l] = pcs[r0 + l].len;
-      for (uint32_t t = 0; t < left[l]; ++t) rows_of[l][t] = sigma[pcs[r0 + l].start + t];
+    for (int l = 0; l < kLanes; ++l) {
+      const int pc = at_place[(size_t)g * kLanes + l];
+      h[l] = pc >= 0 ? slot_ids[pc] : (uint16_t)(kWindow + (l & (kDummySlots - 1)));
     }
-    for (int t = 0; t < n; ++t) {
-      uint16_t* e = add_position(null_index);
-      for (int half = 0; half < 2; ++half) {
-        const int l0 = half * 32, l1 = std::min(cnt, l0 + 32);
-        BankMatch m;
-        m.rows_of = &rows_of[0];
-        m.left = left;
-        m.l0 = l0;
-        for (int i = 0; i < 32; ++i) { m.bank_lane[i] = -1; m.lane_pick[i] = -1; }
-        // lanes with the fewest rows left (the highest lanes) go first
-        for (int l = l1 - 1; l >= l0; --l) {
-          if (left[l] == 0) continue;
-          for (bool& sb : m.seen_bank) sb = false;
-          m.augment(l);
-        }
-        const int* bank_lane = m.bank_lane;
-        const int* lane_pick = m.lane_pick;
-        uint8_t load[32] = {0};
-        for (int i = 0; i < 32; ++i) if (bank_lane[i] >= 0) load[i] = 1;
-        for (int l = l1 - 1; l >= l0; --l) {
-          if (left[l] == 0) continue;
-          uint32_t best;
-          if (lane_pick[l - l0] >= 0) {
-            best = (uint32_t)lane_pick[l - l0];
-          } else {
-            best = 0;
-            for (uint32_t c = 1; c < left[l]; ++c)
-              if (load[rows_of[l][c] & 31] < load[rows_of[l][best] & 31]) best = c;
-            ++load[rows_of[l][best] & 31];
-          }
-          e[l] = rows_of[l][best];
-          rows_of[l][best] = rows_of[l][--left[l]];
-          ++nidx;
-        }
+    const int first = npos;
+    for (int t = 0; t < n; ++t) add_position(null_index);
+    for (int half = 0; half < 2; ++half) {
+      uint16_t row_of[kHalf][kMaxPieceRows], place[kHalf][kMaxPieceRows];
+      int len[kHalf];
+      for (int l = 0; l < kHalf; ++l) {
+        const int pc = at_place[(size_t)g * kLanes + half * kHalf + l];
+        len[l] = plen(pc);
+        for (int t = 0; t < len[l]; ++t) row_of[l][t] = sigma[pcs[pc].start + t];
+        nidx += (uint32_t)len[l];
       }
+      colour_half(n, row_of, len, null_index, place);
+      for (int t = 0; t < n; ++t)
+        for (int l = 0; l < kHalf; ++l) positions[(size_t)(first + t) * kLanes + half * kHalf + l] = place[l][t];
     }
     ++ngroups;
   }

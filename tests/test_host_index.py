@@ -217,16 +217,16 @@ def check_streams(h, S):
                 assert np.all(body <= rows)  # row index or the null index
                 real = body < rows
                 lens = real.sum(axis=0)
-                # a piece occupies the first positions of its lane; pieces are ranked by descending length
-                assert np.all(real == (np.arange(len(idxs))[:, None] < lens[None, :]))
-                assert np.all(np.diff(lens) <= 0) and (last_len is None or lens[0] <= last_len)
+                # a piece may use any of its group's positions (its rows are summed); groups are ranked by
+                # descending piece length: no piece is longer than the shortest piece of the group before
                 owners = lens > 0
-                last_len = lens[owners][-1] if owners.any() else last_len
+                assert last_len is None or lens.max() <= last_len
+                last_len = lens[owners].min() if owners.any() else last_len
                 assert np.all(slots[~owners] >= WINDOW) and np.all(slots[~owners] < OVF_BASE)  # dummies
                 own = slots[owners]
                 assert np.all((own < (1 << kw)) | ((own >= OVF_BASE) & (own < OVF_BASE + LANES * npar)))
                 # only the unit's last group may carry one all-null position (even position count)
-                assert lens[0] >= len(idxs) - (1 if head == groups[-1][0] else 0) and lens[0] >= 1
+                assert lens.max() >= len(idxs) - (1 if head == groups[-1][0] else 0) and lens.max() >= 1
                 used_slots += own.tolist()
                 pieces += int(owners.sum())
                 rr = body[real].tolist()
