@@ -48,3 +48,16 @@ def test_activations():
     small = workloads.CONFIGS[1][0]
     A = small.matrix()
     assert A.shape == (1024, 1024) and np.array_equal(A, small.matrix())
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one device: `bench.py --gpus N` with N > 1 says so and exits with an error."""
+    import os
+    import subprocess
+    import sys
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=120)
+    assert proc.returncode != 0 and proc.stdout.strip() == ""
+    assert "one GPU" in proc.stderr
