@@ -362,3 +362,45 @@ def test_degenerate_matrices(name):
         if name == "bin_k":
             sigma, L = R.rsr_host_export_block(h.x, 0, 0)
             assert sigma.tolist() == list(range(1024)) and L.tolist() == list(range(1025))
+
+
+def gather_passes(S, rows):
+    """LDS passes per half-wavefront gather of float activations (bank = row mod 32): for every index
+    position and half, the largest number of distinct rows that fall into one bank."""
+    units, stream = S["units"], S["stream"]
+    total, count, worst = 0, 0, 0
+    conflict_free_possible, conflict_free = 0, 0
+    for U in units:
+        pos = unit_positions(stream, U)
+        _, groups = unit_groups(U, pos)
+        for head, idxs in groups:
+            body = pos[idxs] if idxs else np.empty((0, LANES), dtype=np.int64)
+            while body.shape[0] and np.all(body[-1] == rows):  # the position that makes the count even
+                body = body[:-1]
+            for half in (0, 1):
+                sub = body[:, 32 * half : 32 * half + 32]
+                real = sub[sub < rows]
+                degree = np.bincount(real % 32, minlength=32).max() if real.size else 0
+                passes = []
+                for t in range(sub.shape[0]):
+                    rr = np.unique(sub[t][sub[t] < rows])
+                    passes.append(max(1, int(np.bincount(rr % 32, minlength=32).max()) if rr.size else 1))
+                total += sum(passes)
+                count += len(passes)
+                worst = max(worst, max(passes, default=1))
+                if sub.shape[0] and degree <= sub.shape[0]:  # no bank has more rows than there are positions
+                    conflict_free_possible += 1
+                    conflict_free += all(x == 1 for x in passes)
+    return total / max(count, 1), worst, conflict_free_possible, conflict_free
+
+
+def test_rows_of_a_half_wavefront_are_spread_over_the_lds_banks():
+    # Random rows in random order cost about 3.5 passes per gather here.  The packer's placement must
+    # stay clearly below, must never need more than two passes where no bank holds more than twice
+    # the positions of its half group, and must be conflict-free wherever that is possible at all.
+    A = make(4096, 80, "binary", 11)
+    with HostIndex(A, 10) as h:
+        S = R.rsr_host_streams(h.x)
+        mean, worst, possible, achieved = gather_passes(S, 4096)
+    assert mean < 2.0 and worst <= 2
+    assert possible > 0 and achieved == possible
