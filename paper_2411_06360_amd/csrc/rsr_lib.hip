@@ -676,17 +676,8 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   if (total(waves) > h->lds_max)
     return fail(RSR_ERR_UNSUPPORTED, "activation vector of " + std::to_string(h->rows) + " rows does not fit in " +
                                          std::to_string(h->lds_max) + " bytes of LDS");
-  const size_t lds = total(waves);
-  p.ucap = (int)ucap; p.nslot = nslot;
-  p.off_win = (uint32_t)vbytes;
-  p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
-  p.off_done = (uint32_t)(p.off_rec + ucap * rec_bytes);
-  p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
-  p.off_bu = p.off_ctr + 16;
-  p.nunits = (int)h->nunits;
-
   // grid: about one (or two, if LDS allows) resident workgroups per compute unit in total
-  int wg_per_cu = h->wg_per_cu > 0 ? h->wg_per_cu : (int)std::min<size_t>(2, h->lds_max / lds);
+  int wg_per_cu = h->wg_per_cu > 0 ? h->wg_per_cu : (int)std::min<size_t>(2, h->lds_max / total(waves));
   if (wg_per_cu < 1) wg_per_cu = 1;
   int64_t g1 = ((int64_t)h->num_cu * wg_per_cu + batch - 1) / batch;
   g1 = (g1 + 7) / 8 * 8;
@@ -695,6 +686,20 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   p.g1 = (int)g1;
   const int64_t grid = (g1 + 7) / 8 * 8 * (int64_t)batch;
   if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
+
+  // no more wavefronts than a workgroup has units: idle ones only lengthen the start of the launch
+  // (small matrices: 5.5 -> 4.3 us for 1024 x 1024)
+  const int64_t units_per_wg = (h->nunits + g1 - 1) / g1;
+  if (units_per_wg < waves) waves = (int)std::max<int64_t>(1, units_per_wg);
+
+  const size_t lds = total(waves);
+  p.ucap = (int)ucap; p.nslot = nslot;
+  p.off_win = (uint32_t)vbytes;
+  p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
+  p.off_done = (uint32_t)(p.off_rec + ucap * rec_bytes);
+  p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
+  p.off_bu = p.off_ctr + 16;
+  p.nunits = (int)h->nunits;
 
   auto kern = rsr_matvec_kernel<VT>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream),
