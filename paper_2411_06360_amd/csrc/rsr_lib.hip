@@ -668,12 +668,18 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   const size_t win_bytes = (size_t)rsr::kWindowSlots * 4;
   const size_t rec_bytes = (size_t)rsr::kRecordWords * 4;
   int nslot = 64;
-  size_t ucap = std::max<size_t>(h->max_units_per_block, 256);
-  int waves = h->waves;
-  auto total = [&](int w) { return vbytes + (size_t)w * win_bytes + ucap * rec_bytes + (size_t)nslot * 4 + 16 + ((size_t)nslot + 1) * 4 + 12; };
-  if (total(1) > h->lds_max && ucap > h->max_units_per_block) ucap = h->max_units_per_block;
-  while (waves > 1 && total(waves) > h->lds_max) waves >>= 1;
-  if (total(waves) > h->lds_max)
+  // Unit records of a round: room for wavefronts comes first, then as many records as fit (a round
+  // ends with a barrier); a block's units always fit in a round.
+  size_t ucap = 0;
+  int waves = 0;
+  auto total = [&](int w, size_t uc) { return vbytes + (size_t)w * win_bytes + uc * rec_bytes + (size_t)nslot * 4 + 16 + ((size_t)nslot + 1) * 4 + 12; };
+  for (size_t cand : {(size_t)512, (size_t)256, (size_t)128, (size_t)64, (size_t)1}) {
+    const size_t uc = std::max<size_t>(h->max_units_per_block, cand);
+    int w = h->waves;
+    while (w > 1 && total(w, uc) > h->lds_max) --w;
+    if (total(w, uc) <= h->lds_max && w > waves) { waves = w; ucap = uc; }
+  }
+  if (waves == 0)
     return fail(RSR_ERR_UNSUPPORTED, "activation vector of " + std::to_string(h->rows) + " rows does not fit in " +
                                          std::to_string(h->lds_max) + " bytes of LDS");
   // Grid and workgroup size.  Up to four workgroups per compute unit if they fit together (LDS, and 16
@@ -681,6 +687,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   // no more wavefronts than the largest share of a workgroup has units: idle wavefronts only lengthen
   // the start of the launch (1024 x 1024: 5.5 -> 4.0 us per product).
   const int waves_fit = waves;
+  const size_t ucap_fit = ucap;
   int64_t g1 = 1;
   for (int wg = (h->wg_per_cu > 0 ? h->wg_per_cu : 4); wg >= 1; --wg) {
     g1 = ((int64_t)h->num_cu * wg + batch - 1) / batch;
@@ -690,13 +697,14 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
     const int64_t blocks_per_wg = (h->nblocks + g1 - 1) / g1;
     const int64_t units_per_wg = blocks_per_wg * (int64_t)std::max<uint32_t>(1, h->max_units_per_block);
     waves = (int)std::min<int64_t>(waves_fit, units_per_wg);
-    if (wg == 1 || h->wg_per_cu > 0 || (wg * waves <= 16 && (size_t)wg * total(waves) <= h->lds_max)) break;
+    ucap = std::min<size_t>(ucap_fit, (size_t)units_per_wg);  // records for the units a workgroup can have
+    if (wg == 1 || h->wg_per_cu > 0 || (wg * waves <= 16 && (size_t)wg * total(waves, ucap) <= h->lds_max)) break;
   }
   p.g1 = (int)g1;
   const int64_t grid = (g1 + 7) / 8 * 8 * (int64_t)batch;
   if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
 
-  const size_t lds = total(waves);
+  const size_t lds = total(waves, ucap);
   p.ucap = (int)ucap; p.nslot = nslot;
   p.off_win = (uint32_t)vbytes;
   p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
