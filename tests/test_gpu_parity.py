@@ -196,6 +196,40 @@ def test_results_are_reproducible_and_batch_equals_single_calls():
         assert np.array_equal(d.matvec(v8), np.stack([d.matvec(v8[i]) for i in range(5)]))
 
 
+def test_product_captured_in_a_graph_gives_the_eager_result_on_every_replay():
+    """rsr_matvec allocates nothing and enqueues one kernel: it can be captured in a HIP graph.  The graph
+    is replayed several times with new activations and eager work in between; every replay must equal the
+    eager product of the same activations bit for bit."""
+    import torch
+
+    g = rng(92)
+    A = g.integers(-1, 2, size=(3000, 500)).astype(np.int8)
+    note("graph capture 3000x500 k=9 batch 3")
+    with DeviceIndex(A, 9) as d:
+        dv = torch.zeros((3, 3000), dtype=torch.float32, device="cuda")
+        out = torch.zeros((3, 500), dtype=torch.float32, device="cuda")
+        eager = torch.zeros_like(out)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):  # warm-up on the capture stream
+            R.rsr_matvec(d.handle, dv, out, 3, side.cuda_stream)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            R.rsr_matvec(d.handle, dv, out, 3, torch.cuda.current_stream().cuda_stream)
+        for rep in range(4):
+            v = g.standard_normal((3, 3000)).astype(np.float32)
+            dv.copy_(torch.from_numpy(v).cuda())
+            R.rsr_matvec(d.handle, dv, eager, 3, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            out.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), f"replay {rep} differs from the eager product"
+            assert_f32_close(out.cpu().numpy(), dense.matvec_f32(A, v), v)
+
+
 def test_unaligned_activation_pointer_and_odd_row_count():
     import torch
 
