@@ -37,8 +37,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 # of known size; summaries under profiles/).  Keyed by (workload, batch, dtype, regime); other
 # combinations report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("binary_16k", 1, "f32", "cold"): 64.93e6,   # profiles/rsr_matvec_f32_binary16k_b1_cold.md
-    ("binary_16k", 8, "f32", "cold"): 72.27e6,   # profiles/rsr_matvec_f32_binary16k_b8_cold.md
+    ("binary_16k", 1, "f32", "cold"): 64.86e6,   # profiles/rsr_matvec_f32_binary16k_b1_cold.md
+    ("binary_16k", 8, "f32", "cold"): 73.97e6,   # profiles/rsr_matvec_f32_binary16k_b8_cold.md
 }
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache; the cold regime rotates over > 2x this
 

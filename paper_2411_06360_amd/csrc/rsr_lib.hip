@@ -695,6 +695,11 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
     if (g1 > h->nblocks) g1 = h->nblocks;
     if (g1 < 1) g1 = 1;
     const int64_t blocks_per_wg = (h->nblocks + g1 - 1) / g1;
+    // Equal shares: no more workgroups than it takes to keep the largest share this small.  (1366 blocks
+    // over 256 compute units would be 5 or 6 blocks each; 228 workgroups get 6 each, 28 compute units
+    // stay idle, and the product is 0.5 us faster: the stream is shared by all compute units and the
+    // workgroups with the larger share finish last either way, only later when more of them compete.)
+    g1 = (h->nblocks + blocks_per_wg - 1) / blocks_per_wg;
     const int64_t units_per_wg = blocks_per_wg * (int64_t)std::max<uint32_t>(1, h->max_units_per_block);
     waves = (int)std::min<int64_t>(waves_fit, units_per_wg);
     ucap = std::min<size_t>(ucap_fit, (size_t)units_per_wg);  // records for the units a workgroup can have
