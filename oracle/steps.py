@@ -18,9 +18,10 @@ Readings taken where the paper is loose (each is checked by a test):
   sort), which reproduces the permutation printed in Example 3.3.
 * Full segmentation (Section 3.3): L[j] is the number of rows whose value is
   below j.  For a value that occurs this is its first sorted position; for one
-  that does not it is the start of the next value that does ("the same boundary
-  is assigned for the next value"), and past the last occurring value it is the
-  row count, which makes the length rule of Proposition 3.5 hold for every j.
+  that does not it is the start of the next value that does (Section 3.3 gives
+  an absent value the boundary of its successor), and past the last occurring
+  value it is the row count, which makes the length rule of Proposition 3.5
+  hold for every j.
 * RSR++ fold (Algorithm 3, Section 4.3): the printed listing indexes the pair
   sums with the outer loop variable and never copies them back; the text of
   Section 4.3 says what is meant.  "Odd indices" are odd when the 2^i entries are
@@ -203,11 +204,10 @@ def fold_rsrpp(u: Sequence, k: int) -> np.ndarray:
 def rsr_binary(v: Sequence, B: np.ndarray, k: int, step2: str = "fold") -> np.ndarray:
     """v . B for binary B by Algorithm 2, with step 2 either the plain product or the RSR++ fold."""
     v = np.asarray(v)
+    sigmas, Ls = preprocess(B, k)  # Algorithm 1, once per matrix
     pieces = []
-    for Bi in column_blocks(B, k):
-        width = Bi.shape[1]
-        sigma = binary_row_order(Bi)
-        L = full_segmentation(Bi)
+    for sigma, L in zip(sigmas, Ls):
+        width = len(L).bit_length() - 1  # L has 2^width entries
         u = segmented_sum(v, sigma, L)
         pieces.append(fold_rsrpp(u, width) if step2 == "fold" else block_product_rsr(u, width))
     return np.concatenate(pieces)

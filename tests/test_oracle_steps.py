@@ -181,3 +181,40 @@ def test_matrix_equal_to_bin_k_isolates_the_fold():
     assert steps.binary_row_order(A).tolist() == list(range(1 << k))
     assert steps.full_segmentation(A).tolist() == list(range(1 << k))
     assert np.array_equal(steps.fold_rsrpp(v.astype(np.int64), k), dense.matvec_i8(A, v))
+
+
+# ---- Algorithm 1 as a whole ----------------------------------------------------------------
+def test_preprocess_reproduces_the_tables_of_the_printed_matrix(golden):
+    """Algorithm 1 on the printed 6x6 B with k = 2: block 1 is Example 3.3 as printed; blocks 2 and 3
+    are worked by hand from the printed B (the fixture says how)."""
+    B = np.array(golden["matrix_B"]["rows"])
+    d = golden["derived_tables_of_B"]
+    sigmas, Ls = steps.preprocess(B, d["k"])
+    assert len(sigmas) == len(Ls) == 3
+    assert [(s + 1).tolist() for s in sigmas] == d["sigma_1based"]
+    assert [(L + 1).tolist() for L in Ls] == d["full_segmentation_1based"]
+    assert (sigmas[0] + 1).tolist() == golden["example_3_3"]["sigma_1based"]
+    assert (Ls[0] + 1).tolist() == golden["example_3_3"]["full_segmentation_1based"]
+
+
+@pytest.mark.parametrize("rows,cols,k", [(1, 1, 1), (9, 7, 3), (40, 10, 4), (33, 17, 5), (64, 6, 6)])
+def test_preprocess_invariants(rows, cols, k):
+    """What Algorithm 1 must deliver whatever the matrix: one (sigma, L) per k-column block (the last
+    block narrower, Definition 3.1); sigma a permutation along which the row values never decrease and
+    equal rows keep their order (Definition 3.2); L with 2^width entries whose differences are the
+    histogram of the row values (Proposition 3.5), computed here by counting, not by sorting."""
+    B = rng(rows * 100 + cols).integers(0, 2, size=(rows, cols))
+    sigmas, Ls = steps.preprocess(B, k)
+    nblocks = -(-cols // k)
+    assert len(sigmas) == len(Ls) == nblocks
+    for i in range(nblocks):
+        width = min(k, cols - i * k)
+        vals = [int("".join(str(int(x)) for x in B[r, i * k : i * k + width]), 2) for r in range(rows)]
+        sigma, L = sigmas[i], Ls[i]
+        assert sorted(sigma.tolist()) == list(range(rows))
+        along = [vals[r] for r in sigma]
+        assert all(a <= b for a, b in zip(along, along[1:]))
+        assert all(r0 < r1 for r0, r1, a, b in zip(sigma, sigma[1:], along, along[1:]) if a == b)
+        assert len(L) == 1 << width
+        ends = L.tolist()[1:] + [rows]
+        assert [e - s for s, e in zip(L.tolist(), ends)] == [vals.count(j) for j in range(1 << width)]
