@@ -45,9 +45,9 @@ class RsrInfo(ctypes.Structure):
 # numpy view of the 32-byte unit descriptors (csrc/rsr_format.h)
 UNIT_DTYPE = np.dtype(
     [
-        ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("npar", "u1"),
-        ("units_in_block", "<u2"), ("npos", "u1"), ("ngroups", "u1"),
-        ("hdr_lo", "<u4"), ("hdr_hi", "<u2"), ("index_in_block", "<u2"), ("nidx", "<u4"), ("npieces", "<u4"),
+        ("stream_off", "<u4"), ("block", "<u4"), ("window", "<u2"), ("part", "u1"), ("npos", "u1"),
+        ("units_in_block", "<u2"), ("index_in_block", "<u2"), ("slot0", "<u2"), ("reserved0", "<u2"),
+        ("nrows", "<u4"), ("nheads", "<u4"), ("nentries", "<u4"),
     ]
 )
 assert UNIT_DTYPE.itemsize == 32

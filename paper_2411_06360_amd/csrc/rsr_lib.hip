@@ -7,10 +7,13 @@
 //   * Its wavefronts take work units (one window of 2^kw row values of one block and part, see
 //     rsr_format.h) from an LDS counter.  For a unit a wavefront
 //       1. reads the unit's stream with 16-byte buffer loads (the next unit's loads go out while
-//          the current one is summed) and walks its positions: at an index position every lane
-//          gathers v[sigma(p)] from LDS into its running sum - the segmented sums of Eq. SS2, one
-//          piece of a segment per lane - and at a header position drops the sum into the slot of
-//          its private window of u in LDS (plain stores: every slot has one writer);
+//          the current one is summed) and walks its positions: every lane owns a run of
+//          consecutive sorted rows and gathers v[sigma(p)] from LDS into its running sum - the
+//          segmented sums of Eq. SS2 - and where a row's flag says that a new value starts it
+//          first drops the sum into the current slot of its private window of u in LDS and moves
+//          to the next slot (plain stores: a slot is stored by the lane in which its segment
+//          ends; the part of a segment that a lane is left with at the end of its run is added
+//          to the slot afterwards);
 //       2. reads the window back in value order;
 //       3. takes the low kw levels of the RSR++ fold (Section 4.3, Algorithm 3): "sum the
 //          odd-indexed entries, then add neighbours" - three levels inside a lane's 8 consecutive
@@ -68,7 +71,7 @@ struct rsr_handle {
   int k = 0, kw = 0, parts = 0, last_width = 0;
   uint32_t max_units_per_block = 0;
   int64_t stored_rows = 0, segments = 0, nunits = 0;
-  int64_t header_positions = 0;
+  int64_t flag_bytes = 0;
   size_t stream_bytes = 0, unit_bytes = 0, blk_bytes = 0;
   // device tables
   void* d_stream = nullptr;
@@ -97,7 +100,7 @@ void fill_info(const rsr::Packed& P, rsr_info_t* info) {
   info->nblocks = P.nblocks; info->last_block_width = P.last_width;
   info->lo_bits = P.kw; info->hi_bits = P.k - P.kw;
   info->stored_rows = P.stored_rows; info->segments = P.segments; info->work_units = (int64_t)P.units.size();
-  info->segment_bytes = P.header_positions * rsr::kPositionBytes;
+  info->segment_bytes = P.flag_bytes;
   info->index_bytes = (int64_t)(P.stream.size() * sizeof(uint16_t)) - info->segment_bytes;
   info->schedule_bytes = (int64_t)(P.units.size() * sizeof(rsr::Unit) + P.blk_unit.size() * sizeof(uint32_t));
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
@@ -129,22 +132,17 @@ template <int CTRL, int ROW_MASK, int BANK_MASK>
 __device__ __forceinline__ int dpp_get(int x) {
   return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, BANK_MASK, false);
 }
-// Lanes whose DPP source does not exist, or that the masks exclude, receive 0.
-template <typename AT>
-__device__ __forceinline__ AT wave_sum_to_lane63(AT x) {
-  AT y = x + dpp_get<0x111, 0xf, 0xf>(x);   // row_shr:1
-  y += dpp_get<0x112, 0xf, 0xf>(x);         // row_shr:2
-  y += dpp_get<0x113, 0xf, 0xf>(x);         // row_shr:3   -> y[i] = x[i-3..i]
-  y += dpp_get<0x114, 0xf, 0xe>(y);         // row_shr:4, lanes 4..15 of each row
-  y += dpp_get<0x118, 0xf, 0xc>(y);         // row_shr:8, lanes 8..15 -> lane 15 holds the row's sum
-  y += dpp_get<0x142, 0xa, 0xf>(y);         // row_bcast:15 into rows 1 and 3
-  y += dpp_get<0x143, 0xc, 0xf>(y);         // row_bcast:31 into rows 2 and 3 -> lane 63 holds all
+// Inclusive prefix sum over the 64 lanes.  Lanes whose DPP source does not exist, or that the
+// masks exclude, receive 0.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+  int y = x + dpp_get<0x111, 0xf, 0xf>(x);   // row_shr:1
+  y += dpp_get<0x112, 0xf, 0xf>(x);           // row_shr:2
+  y += dpp_get<0x113, 0xf, 0xf>(x);           // row_shr:3   -> y[i] = x[i-3..i]
+  y += dpp_get<0x114, 0xf, 0xe>(y);           // row_shr:4, lanes 4..15 of each row
+  y += dpp_get<0x118, 0xf, 0xc>(y);           // row_shr:8, lanes 8..15 -> prefix sums inside each row of 16
+  y += dpp_get<0x142, 0xa, 0xf>(y);           // row_bcast:15 into rows 1 and 3
+  y += dpp_get<0x143, 0xc, 0xf>(y);           // row_bcast:31 into rows 2 and 3
   return y;
-}
-
-template <typename AT>
-__device__ __forceinline__ AT read_lane(AT x, int l) {
-  return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), l));
 }
 
 // Sums of eight values over the 16 lanes of each DPP row, all at once: after every exchange a
@@ -210,28 +208,29 @@ template <> struct Acc<float> { using type = float; };
 template <> struct Acc<int8_t> { using type = int32_t; };
 
 // ---- the stream positions of a unit, eight (one granule) or two (one dword) at a time ----
-// Per position and lane the stream holds a uint16 x.  At a header position (bit set in `hb`) the
-// running sum `a` of the group that ends here goes to the window slot the lane was given at the
-// group's own header (LDS byte address `sa`), x names the next slot and the sum restarts; at any
-// other position the activation with row index x is added.  All eight gathers are issued before
-// the first sum so that their latencies overlap.  Written in assembly because the compiler turns
-// the per-position choice into long chains of scalar bookkeeping: here a position costs one
-// address extraction, one LDS read, one bit test, one branch and one add.
+// Per position and lane the stream holds a row index x (uint16) and a flag, the top bit of `f`
+// (f is shifted left by one per position).  A flagged entry starts a new value: the running sum
+// `a` of the segment that ends here goes to the current window slot (LDS byte address `sa`), the
+// lane moves to the next slot and the sum restarts; then, flagged or not, the activation with row
+// index x is added.  All eight gathers are issued before the first sum so that their latencies
+// overlap.  Written in assembly: a position costs one address extraction, one LDS read, one
+// add-with-carry that shifts the flags and puts the flag of every lane into vcc, three
+// instructions under that mask (store, next slot, restart) and one add; there are no branches.
+// (The wait before the add of position q allows 7 - q LDS operations to be outstanding: the
+// gathers behind it, whether or not the stores of masked-off lanes are counted.)
 //   float activations:  LDS byte address of row x = 4 * x (the vector sits at LDS offset 0)
 //   int8 activations:   LDS byte address of row x = x
 #define RSR_X4_LO(d, w) "v_lshlrev_b32_sdwa " d ", 2, " w " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0\n"
 #define RSR_X4_HI(d, w) "v_lshlrev_b32_sdwa " d ", 2, " w " dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_1\n"
 #define RSR_X1_LO(d, w) "v_and_b32 " d ", 0xffff, " w "\n"
 #define RSR_X1_HI(d, w) "v_lshrrev_b32 " d ", 16, " w "\n"
-#define RSR_POS(q, cnt, ADD) \
-  "s_bitcmp1_b32 %[hb], " #q "\n s_cbranch_scc1 .Lh" #q "_%=\n s_waitcnt lgkmcnt(" #cnt ")\n " ADD " %[a], %[a], %[t" #q "]\n .Lc" #q "_%=:\n"
-#define RSR_HDR_F32(q) \
-  ".Lh" #q "_%=:\n ds_write_b32 %[sa], %[a]\n v_add_u32 %[sa], %[wb], %[s" #q "]\n v_mov_b32 %[a], 0\n s_branch .Lc" #q "_%=\n"
-#define RSR_HDR_I8(q) \
-  ".Lh" #q "_%=:\n ds_write_b32 %[sa], %[a]\n v_lshl_add_u32 %[sa], %[s" #q "], 2, %[wb]\n v_mov_b32 %[a], 0\n s_branch .Lc" #q "_%=\n"
+#define RSR_POS(q, cnt, ADD)                                                                             \
+  "v_add_co_u32 %[f], vcc, %[f], %[f]\n s_mov_b64 exec, vcc\n ds_write_b32 %[sa], %[a]\n"              \
+  "v_add_u32 %[sa], 4, %[sa]\n v_mov_b32 %[a], 0\n s_mov_b64 exec, -1\n s_waitcnt lgkmcnt(" #cnt ")\n " \
+  ADD " %[a], %[a], %[t" #q "]\n"
 
-__device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, float& a,
-                                             uint32_t& sa, uint32_t wb, const float*) {
+__device__ __forceinline__ void granule_step(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, float& a, uint32_t& sa,
+                                             uint32_t& f, const float*) {
   uint32_t s0, s1, s2, s3, s4, s5, s6, s7;
   float t0, t1, t2, t3, t4, t5, t6, t7;
   asm volatile(
@@ -241,31 +240,33 @@ __device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t 
       "ds_read_b32 %[t4], %[s4]\n ds_read_b32 %[t5], %[s5]\n ds_read_b32 %[t6], %[s6]\n ds_read_b32 %[t7], %[s7]\n"
       RSR_POS(0, 7, "v_add_f32") RSR_POS(1, 6, "v_add_f32") RSR_POS(2, 5, "v_add_f32") RSR_POS(3, 4, "v_add_f32")
       RSR_POS(4, 3, "v_add_f32") RSR_POS(5, 2, "v_add_f32") RSR_POS(6, 1, "v_add_f32") RSR_POS(7, 0, "v_add_f32")
-      "s_branch .Lend_%=\n"
-      RSR_HDR_F32(0) RSR_HDR_F32(1) RSR_HDR_F32(2) RSR_HDR_F32(3) RSR_HDR_F32(4) RSR_HDR_F32(5) RSR_HDR_F32(6) RSR_HDR_F32(7)
-      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
-      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3), [s4] "=&v"(s4),
-        [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
-        [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
-      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
-      : "scc", "memory");
+      : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3),
+        [s4] "=&v"(s4), [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),
+        [t3] "=&v"(t3), [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
+      : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
+      : "vcc", "memory");
 }
-__device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, float& a, uint32_t& sa, uint32_t wb, const float*) {
+__device__ __forceinline__ void pair_step(uint32_t w0, float& a, uint32_t& sa, uint32_t& f, const float*) {
   uint32_t s0, s1;
   float t0, t1;
   asm volatile(
       RSR_X4_LO("%[s0]", "%[w0]") RSR_X4_HI("%[s1]", "%[w0]")
       "ds_read_b32 %[t0], %[s0]\n ds_read_b32 %[t1], %[s1]\n"
       RSR_POS(0, 1, "v_add_f32") RSR_POS(1, 0, "v_add_f32")
-      "s_branch .Lend_%=\n"
-      RSR_HDR_F32(0) RSR_HDR_F32(1)
-      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
-      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
-      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0)
-      : "scc", "memory");
+      : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [w0] "v"(w0)
+      : "vcc", "memory");
 }
-__device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, int32_t& a,
-                                             uint32_t& sa, uint32_t wb, const int8_t*) {
+__device__ __forceinline__ void single_step(uint32_t w0, float& a, uint32_t& sa, uint32_t& f, const float*) {
+  uint32_t s0;
+  float t0;
+  asm volatile(RSR_X4_LO("%[s0]", "%[w0]") "ds_read_b32 %[t0], %[s0]\n" RSR_POS(0, 0, "v_add_f32")
+               : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [t0] "=&v"(t0)
+               : [w0] "v"(w0)
+               : "vcc", "memory");
+}
+__device__ __forceinline__ void granule_step(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3, int32_t& a, uint32_t& sa,
+                                             uint32_t& f, const int8_t*) {
   uint32_t s0, s1, s2, s3, s4, s5, s6, s7;
   int32_t t0, t1, t2, t3, t4, t5, t6, t7;
   asm volatile(
@@ -275,28 +276,22 @@ __device__ __forceinline__ void granule_step(uint32_t hb, uint32_t w0, uint32_t 
       "ds_read_i8 %[t4], %[s4]\n ds_read_i8 %[t5], %[s5]\n ds_read_i8 %[t6], %[s6]\n ds_read_i8 %[t7], %[s7]\n"
       RSR_POS(0, 7, "v_add_u32") RSR_POS(1, 6, "v_add_u32") RSR_POS(2, 5, "v_add_u32") RSR_POS(3, 4, "v_add_u32")
       RSR_POS(4, 3, "v_add_u32") RSR_POS(5, 2, "v_add_u32") RSR_POS(6, 1, "v_add_u32") RSR_POS(7, 0, "v_add_u32")
-      "s_branch .Lend_%=\n"
-      RSR_HDR_I8(0) RSR_HDR_I8(1) RSR_HDR_I8(2) RSR_HDR_I8(3) RSR_HDR_I8(4) RSR_HDR_I8(5) RSR_HDR_I8(6) RSR_HDR_I8(7)
-      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
-      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3), [s4] "=&v"(s4),
-        [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
-        [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
-      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
-      : "scc", "memory");
+      : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [s1] "=&v"(s1), [s2] "=&v"(s2), [s3] "=&v"(s3),
+        [s4] "=&v"(s4), [s5] "=&v"(s5), [s6] "=&v"(s6), [s7] "=&v"(s7), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2),
+        [t3] "=&v"(t3), [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7)
+      : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3)
+      : "vcc", "memory");
 }
-__device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, uint32_t& sa, uint32_t wb, const int8_t*) {
+__device__ __forceinline__ void pair_step(uint32_t w0, int32_t& a, uint32_t& sa, uint32_t& f, const int8_t*) {
   uint32_t s0, s1;
   int32_t t0, t1;
   asm volatile(
       RSR_X1_LO("%[s0]", "%[w0]") RSR_X1_HI("%[s1]", "%[w0]")
       "ds_read_i8 %[t0], %[s0]\n ds_read_i8 %[t1], %[s1]\n"
       RSR_POS(0, 1, "v_add_u32") RSR_POS(1, 0, "v_add_u32")
-      "s_branch .Lend_%=\n"
-      RSR_HDR_I8(0) RSR_HDR_I8(1)
-      ".Lend_%=:\n s_waitcnt lgkmcnt(0)\n"
-      : [a] "+v"(a), [sa] "+v"(sa), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
-      : [hb] "s"(hb), [wb] "s"(wb), [w0] "v"(w0)
-      : "scc", "memory");
+      : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [s1] "=&v"(s1), [t0] "=&v"(t0), [t1] "=&v"(t1)
+      : [w0] "v"(w0)
+      : "vcc", "memory");
 }
 
 // The scalar fields of a unit descriptor.  The unit number is wavefront-uniform, so the descriptor is
@@ -304,24 +299,31 @@ __device__ __forceinline__ void pair_step(uint32_t hb, uint32_t w0, int32_t& a, 
 // return in the order they were issued across all its wavefronts - a descriptor that has to come
 // from memory would hold back everything requested after it (the other wavefronts' share of the
 // activation vector at the start, stream data later).
+__device__ __forceinline__ void single_step(uint32_t w0, int32_t& a, uint32_t& sa, uint32_t& f, const int8_t*) {
+  uint32_t s0;
+  int32_t t0;
+  asm volatile(RSR_X1_LO("%[s0]", "%[w0]") "ds_read_i8 %[t0], %[s0]\n" RSR_POS(0, 0, "v_add_u32")
+               : [a] "+v"(a), [sa] "+v"(sa), [f] "+v"(f), [s0] "=&v"(s0), [t0] "=&v"(t0)
+               : [w0] "v"(w0)
+               : "vcc", "memory");
+}
+
 struct Desc {
-  uint32_t stream_off, block, hdr_lo, hdr_hi;
-  int window, part, npar, units_in_block, npos, index_in_block;
+  uint32_t stream_off, block;
+  int window, part, npos, units_in_block, index_in_block, slot0;
 };
 __device__ __forceinline__ Desc load_desc(const uint32_t* __restrict__ unit_words, uint32_t u) {
   const uint32_t* w = unit_words + (size_t)__builtin_amdgcn_readfirstlane((int)u) * 8;
   Desc d;
   d.stream_off = w[0];
   d.block = w[1];
-  const uint32_t w2 = w[2], w3 = w[3], w5 = w[5];
+  const uint32_t w2 = w[2], w3 = w[3], w4 = w[4];
   d.window = (int)(w2 & 0xffffu);
   d.part = (int)((w2 >> 16) & 0xffu);
-  d.npar = (int)(w2 >> 24);
+  d.npos = (int)(w2 >> 24);
   d.units_in_block = (int)(w3 & 0xffffu);
-  d.npos = (int)((w3 >> 16) & 0xffu);
-  d.hdr_lo = w[4];
-  d.hdr_hi = w5 & 0xffffu;
-  d.index_in_block = (int)(w5 >> 16);
+  d.index_in_block = (int)(w3 >> 16);
+  d.slot0 = (int)(w4 & 0xffffu);
   return d;
 }
 
@@ -351,27 +353,30 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   const int blk_end = (int)((int64_t)(g + 1) * p.nblocks / p.g1);
   if (blk_begin >= blk_end) return;
 
-  const uint32_t winbase = p.off_win + (uint32_t)wave * (rsr::kWindowSlots * 4);
+  const uint32_t winbase = p.off_win + (uint32_t)wave * (rsr::kWindow * 4);
   AT* win = reinterpret_cast<AT*>(lds + winbase);
   AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
   unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
   unsigned* ctr = reinterpret_cast<unsigned*>(lds + p.off_ctr);
   uint32_t* bu = reinterpret_cast<uint32_t*>(lds + p.off_bu);  // first unit of the round's blocks
   AT* outp = out + (int64_t)b * p.cols;
-  const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u;
+  const uint32_t lane16 = (uint32_t)lane * 16u, lane4 = (uint32_t)lane * 4u, lane2 = (uint32_t)lane * 2u;
 
   // Two register buffers: while one unit is summed from one, the next unit's stream arrives in the
   // other.  Every unit issues the same number of loads (the ones it does not need read the first
   // bytes of the stream, which stay cached), so that the wait counts between units are exact and a
   // wait for the current unit never waits for the next one.
   uint32_t eA[NG][4], eB[NG][4];
-  uint32_t tA[3], tB[3];  // positions behind the last full granule: up to three rows of dwords
+  uint32_t tA[4], tB[4];  // positions behind the last full granule: up to three rows of dwords and one of uint16
+  uint32_t fA[2], fB[2];  // the lane's flags: positions 0..31 from bit 31 down, positions 32..47 from bit 15 down
   // A unit's stream is read through a buffer descriptor that covers exactly the unit: a load past
-  // its end (a granule or a dword row the unit does not have, or a unit that does not exist:
-  // npos = 0) returns zeros without touching memory, and an address costs no vector arithmetic.
+  // its end (a granule, a dword row or the second flag word the unit does not have, or a unit that
+  // does not exist: npos = 0) returns zeros without touching memory, and an address costs no
+  // vector arithmetic.
   auto unit_rsrc = [&](uint32_t stream_off, int npos) {
     unsigned char* us = const_cast<unsigned char*>(stream) + (size_t)stream_off * rsr::kStreamAlign;
-    return __builtin_amdgcn_make_buffer_rsrc(us, 0, npos * rsr::kPositionBytes, 0x00020000);
+    const int bytes = npos * rsr::kPositionBytes + (npos > 0 ? rsr::kFlagBytes0 : 0) + (npos > 32 ? rsr::kFlagBytes1 : 0);
+    return __builtin_amdgcn_make_buffer_rsrc(us, 0, bytes, 0x00020000);
   };
   constexpr int kNonTemporal = 2;  // the stream is read once per product: keep it from displacing reused data
   // (the offsets go into the per-lane offset, which the range check covers; the scalar offset stays 0)
@@ -380,15 +385,27 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)(gq < 4 ? lane16 : lane16_hi) + (gq & 3) * 1024, 0, kNonTemporal);
     e[gq][0] = x.x; e[gq][1] = x.y; e[gq][2] = x.z; e[gq][3] = x.w;
   };
-  auto issue_pair = [&](__amdgpu_buffer_rsrc_t rs, uint32_t pair_base, int j, uint32_t (&et)[3]) {
+  auto issue_pair = [&](__amdgpu_buffer_rsrc_t rs, uint32_t pair_base, int j, uint32_t (&et)[4]) {
     et[j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)pair_base + j * 256, 0, kNonTemporal);
   };
-  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[3]) {
+  // the last position of an odd count: a row of uint16 behind the dword rows (for an even count this
+  // reads flag bytes, which nobody uses)
+  auto issue_single = [&](__amdgpu_buffer_rsrc_t rs, int npos, uint32_t (&et)[4]) {
+    et[3] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, (int)((uint32_t)(npos & ~1) * rsr::kPositionBytes + lane2), 0, kNonTemporal);
+  };
+  auto issue_flags = [&](__amdgpu_buffer_rsrc_t rs, int npos, uint32_t (&f)[2]) {
+    const uint32_t fbase = (uint32_t)npos * rsr::kPositionBytes;
+    f[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(fbase + lane4), 0, kNonTemporal);
+    f[1] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, (int)(fbase + rsr::kFlagBytes0 + lane2), 0, kNonTemporal);
+  };
+  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[4], uint32_t (&f)[2]) {
     const __amdgpu_buffer_rsrc_t rs = unit_rsrc(stream_off, npos);
+    issue_flags(rs, npos, f);
 #pragma unroll
     for (int gq = 0; gq < NG; ++gq) issue_granule(rs, gq, e);
 #pragma unroll
     for (int j = 0; j < 3; ++j) issue_pair(rs, lane4 + (uint32_t)(npos >> 3) * 1024u, j, et);
+    issue_single(rs, npos, et);
   };
 
   // The activation vector is staged first: its loads go out before anything else so that they do
@@ -432,7 +449,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     // behind it in the queue anyway.
     const uint32_t u_first = u_begin + (uint32_t)wave;
     Desc D = load_desc(unit_words, u_first < (uint32_t)p.nunits ? u_first : 0u);
-    issue(D.stream_off, D.npos, eA, tA);
+    issue(D.stream_off, D.npos, eA, tA, fA);
     if (first_round) {
       // vl[rows] = 0 serves the null row index.
       uint4* l16 = reinterpret_cast<uint4*>(vl);
@@ -465,8 +482,9 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     };
     uint32_t ix = (uint32_t)wave;
 
-    // One unit from buffer (e, et); the next unit's stream goes into (en, etn) meanwhile.
-    auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[3], uint32_t (&en)[NG][4], uint32_t (&etn)[3]) {
+    // One unit from buffer (e, et, f); the next unit's stream goes into (en, etn, fn) meanwhile.
+    auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[4], uint32_t (&f)[2], uint32_t (&en)[NG][4], uint32_t (&etn)[4],
+                    uint32_t (&fn)[2]) {
       const uint32_t ix1 = take();
       Desc D1 = fetch_desc(ix1);
       // (the next unit's descriptor arrives during the first granules; its loads go out one by one
@@ -475,27 +493,29 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 
       // ---- step 1: segmented sums (Eq. SS2) into the window (u of Algorithm 2, this window's slice) ----
       {
-        // the window and the overflow slots in use (nobody reads the dummies)
         uint4* w16 = reinterpret_cast<uint4*>(win);
         w16[lane] = make_uint4(0, 0, 0, 0);
         w16[lane + 64] = make_uint4(0, 0, 0, 0);
-        static_assert(rsr::kWindow == 512 && rsr::kOverflowBase % 4 == 0 && rsr::kMaxOverflow <= 256, "zeroing below");
-        if (lane < 16 * D.npar) w16[rsr::kOverflowBase / 4 + lane] = make_uint4(0, 0, 0, 0);
+        static_assert(rsr::kWindow == 512, "zeroing above");
       }
+      // The lane's first slot: the unit's first slot plus the flags of the lanes before it.
+      const uint32_t f1 = f[1] << 16;
+      const int nflag = __builtin_popcount(f[0]) + __builtin_popcount(f1);
+      const int flags_before = wave_inclusive_scan(nflag) - nflag;
+      uint32_t sa = winbase + (uint32_t)(D.slot0 + flags_before) * 4u;
       AT a = (AT)0;
-      uint32_t sa = winbase + (uint32_t)(rsr::kWindow + (lane & (rsr::kDummySlots - 1))) * 4u;  // nothing to deliver yet
       const int full = D.npos >> 3;
+      uint32_t fl = f[0];
       auto step = [&](int gq) {
-        if (gq < full) {
-          const uint32_t hb = ((gq < 4 ? D.hdr_lo : D.hdr_hi) >> (8 * (gq & 3))) & 0xffu;
-          granule_step(hb, e[gq][0], e[gq][1], e[gq][2], e[gq][3], a, sa, winbase, vl);
-        }
+        if (gq == 4) fl = f1;
+        if (gq < full) granule_step(e[gq][0], e[gq][1], e[gq][2], e[gq][3], a, sa, fl, vl);
       };
 #pragma unroll
       for (int gq = 0; gq < NG / 2; ++gq) step(gq);
       if (ix1 >= n_tot) D1.npos = 0;
       const __amdgpu_buffer_rsrc_t rs1 = unit_rsrc(D1.stream_off, D1.npos);
       const uint32_t pair_base1 = lane4 + (uint32_t)(D1.npos >> 3) * 1024u;
+      issue_flags(rs1, D1.npos, fn);
 #pragma unroll
       for (int gq = NG / 2; gq < NG; ++gq) {
         step(gq);
@@ -503,16 +523,37 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
         issue_granule(rs1, 2 * (gq - NG / 2) + 1, en);
       }
       {
+        // the positions behind the last full granule; their flags follow those of the granules
         const int pairs = (D.npos & 7) >> 1;
-        const uint64_t hdr = ((uint64_t)D.hdr_hi << 32) | D.hdr_lo;
-        const uint32_t tm = (uint32_t)(hdr >> (8 * full));
+        fl = (full < 4) ? (f[0] << (8 * full)) : (f1 << (8 * (full - 4)));
 #pragma unroll
         for (int j = 0; j < 3; ++j) {
-          if (j < pairs) pair_step((tm >> (2 * j)) & 3u, et[j], a, sa, winbase, vl);
+          if (j < pairs) pair_step(et[j], a, sa, fl, vl);
           issue_pair(rs1, pair_base1, j, etn);
         }
+        if (D.npos & 1) single_step(et[3], a, sa, fl, vl);
+        issue_single(rs1, D1.npos, etn);
       }
-      *reinterpret_cast<AT*>(lds + sa) = a;  // the last group
+      // What a lane is left with belongs to a segment that goes on in the next lane (or ends with
+      // the unit): it is added to its slot, which by now holds what the lane that saw the end of the
+      // segment has stored there (or zero).  Consecutive lanes without any flag share a slot: their
+      // sums are first added up along the lanes, and the last lane of such a run adds the total.
+      {
+        const bool owner = (nflag > 0) || (lane == 0);
+        const bool has = (a != (AT)0);
+        if (__builtin_amdgcn_ballot_w64(!owner && has) != 0) {
+#pragma unroll
+          for (int d = 1; d < 64; d *= 2) {
+            const AT oa = __shfl_up(a, d);
+            const uint32_t osa = (uint32_t)__shfl_up((int)sa, d);
+            if (lane >= d && osa == sa) a += oa;
+          }
+          const uint32_t nsa = (uint32_t)__shfl_down((int)sa, 1);
+          if (lane == 63 || nsa != sa) *reinterpret_cast<AT*>(lds + sa) += a;
+        } else if (owner) {
+          *reinterpret_cast<AT*>(lds + sa) += a;
+        }
+      }
 
       // ---- step 2: the low levels of the RSR++ fold on this window ----
       // lane l holds the values 8l .. 8l+7 of the window: three levels in registers ...
@@ -524,12 +565,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
         for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
       }
-      // the overflow sums, read in the same LDS round trip (unused overflow slots hold 0; slots
-      // beyond the cleared range are not read)
-      AT ovf[rsr::kMaxOverflow / 64];
-#pragma unroll
-      for (int c = 0; c < rsr::kMaxOverflow / 64; ++c)
-        ovf[c] = (c < D.npar) ? win[rsr::kOverflowBase + c * 64 + lane] : (AT)0;
       // vals[0..2]: the three levels inside the lane; vals[3..6]: lane bits 0..3 (value bits 3..6);
       // vals[7]: the lane's total, from which the two row-index bits (value bits 7, 8) and the
       // window total follow.
@@ -542,29 +577,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 #pragma unroll
       for (int beta = 0; beta < 4; ++beta) vals[3 + beta] = ((lane >> beta) & 1) ? x : (AT)0;
       vals[7] = x;
-      if (D.npar > 0) {
-        // further pieces of segments: their sums sit in overflow slots and count wherever the bits of
-        // the segment's value (the parent, listed in the first positions of the stream) say so.
-        // Bits 0..6 are picked here; the lane that folds an overflow slot lies in the 16-lane row
-        // that stands for the parent's bits 7 and 8, so adding to the lane's total settles those.
-        const uint32_t parw0 = (full > 0) ? e[0][0] : et[0];
-        const uint32_t parw1 = (full > 0) ? e[0][1] : et[1];
-#pragma unroll
-        for (int c = 0; c < rsr::kMaxOverflow / 64; ++c) {
-          if (c < D.npar) {
-            const AT val = ovf[c];
-            const uint32_t pw = (c < 2) ? parw0 : parw1;
-            const uint32_t par = (c & 1) ? (pw >> 16) : (pw & 0xffffu);
-            const uint32_t vbits = __builtin_bit_cast(uint32_t, val);
-#pragma unroll
-            for (int beta = 0; beta < 7; ++beta) {  // val where the bit is set, +0 elsewhere
-              const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)par, beta, 1);
-              vals[beta] += __builtin_bit_cast(AT, vbits & m);
-            }
-            vals[7] += val;
-          }
-        }
-      }
       // Sums over the 16 lanes of each row, then across the four rows with lane swaps: total
       // (all rows), value bit 7 (rows 1 and 3) and value bit 8 (rows 2 and 3).
       const uint32_t rowsum = __builtin_bit_cast(uint32_t, row_sums_of_eight<AT>(vals, lane));
@@ -630,9 +642,9 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     };
 
     while (ix < n_tot) {
-      unit(eA, tA, eB, tB);
+      unit(eA, tA, fA, eB, tB, fB);
       if (ix >= n_tot) break;
-      unit(eB, tB, eA, tA);
+      unit(eB, tB, fB, eA, tA, fA);
       if (ix >= n_tot) break;
     }
     rb0 = rb1;
@@ -665,7 +677,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
 
   // LDS budget: activation vector + per-wavefront windows + unit records + counters
   const size_t vbytes = align_up(((size_t)h->rows + 1) * sizeof(VT), 16);
-  const size_t win_bytes = (size_t)rsr::kWindowSlots * 4;
+  const size_t win_bytes = (size_t)rsr::kWindow * 4;
   const size_t rec_bytes = (size_t)rsr::kRecordWords * 4;
   int nslot = 64;
   // Unit records of a round: room for wavefronts comes first, then as many records as fit (a round
@@ -778,7 +790,7 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   h->k = P.k; h->kw = P.kw; h->parts = P.parts; h->last_width = P.last_width;
   h->max_units_per_block = P.max_units_per_block;
   h->stored_rows = P.stored_rows; h->segments = P.segments; h->nunits = (int64_t)P.units.size();
-  h->header_positions = P.header_positions;
+  h->flag_bytes = P.flag_bytes;
   h->waves = env_int("RSR_WAVES", 16);
   if (h->waves < 1) h->waves = 1;
   if (h->waves > 16) h->waves = 16;
@@ -818,7 +830,7 @@ int rsr_info(const rsr_handle* h, rsr_info_t* info) {
   info->nblocks = h->nblocks; info->last_block_width = h->last_width;
   info->lo_bits = h->kw; info->hi_bits = h->k - h->kw;
   info->stored_rows = h->stored_rows; info->segments = h->segments; info->work_units = h->nunits;
-  info->segment_bytes = h->header_positions * rsr::kPositionBytes;
+  info->segment_bytes = h->flag_bytes;
   info->index_bytes = (int64_t)h->stream_bytes - info->segment_bytes;
   info->schedule_bytes = (int64_t)(h->unit_bytes + h->blk_bytes);
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;

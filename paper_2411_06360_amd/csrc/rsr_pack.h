@@ -16,12 +16,12 @@ struct Packed {
   int64_t rows = 0, cols = 0;
   int k = 0, kw = 0, parts = 0, last_width = 0;
   int64_t nblocks = 0;
-  std::vector<uint16_t> stream;    // unit streams (headers and row indices), 128 elements per position pair
+  std::vector<uint16_t> stream;    // unit streams (row indices in sorted order, then their flags)
   std::vector<Unit> units;
   std::vector<uint32_t> blk_unit;  // nblocks + 1
   int64_t stored_rows = 0;         // real (non-null) row indices in `stream`
-  int64_t segments = 0;            // pieces
-  int64_t header_positions = 0;    // positions that hold slot ids rather than row indices
+  int64_t segments = 0;            // runs of equal rows as stored (a run cut by a unit boundary counts twice)
+  int64_t flag_bytes = 0;          // bytes of `stream` that hold flags rather than row indices
   uint32_t max_units_per_block = 0;
 };
 

@@ -18,7 +18,7 @@ from oracle import dense, steps
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 # layout constants of csrc/rsr_format.h
-WINDOW, DUMMY, OVF_BASE, MAX_OVF, WIN_SLOTS, LANES, MAX_POS, ALIGN = 512, 8, 520, 256, 776, 64, 48, 256
+WINDOW, LANES, MAX_POS, ALIGN = 512, 64, 48, 128
 
 
 def rng(seed):
@@ -148,8 +148,14 @@ def test_ternary_without_minus_ones_is_binary_and_negative_only_is_ternary():
 
 
 # ---- the packed streams: what the kernels rely on ----------------------------------------------------
+def unit_bytes(npos):
+    raw = npos * 2 * LANES + (4 * LANES if npos else 0) + (2 * LANES if npos > 32 else 0)
+    return -(-raw // ALIGN) * ALIGN
+
+
 def unit_positions(stream, U):
-    """The unit's stream as an array [position][lane], undoing the granule order of the device."""
+    """The unit's row indices as an array [position][lane] and its flags [position][lane], undoing the
+    granule order of the device."""
     npos = int(U["npos"])
     base = int(U["stream_off"]) * (ALIGN // 2)
     full = npos // 8
@@ -158,23 +164,30 @@ def unit_positions(stream, U):
         g = stream[base : base + full * 8 * LANES].reshape(full, LANES, 8)
         pos[: full * 8] = g.transpose(0, 2, 1).reshape(full * 8, LANES)
     rest = npos - full * 8
-    if rest:
-        t = stream[base + full * 8 * LANES : base + npos * LANES].reshape(rest // 2, LANES, 2)
-        pos[full * 8 :] = t.transpose(0, 2, 1).reshape(rest, LANES)
-    return pos
+    if rest // 2:
+        t = stream[base + full * 8 * LANES : base + (full * 8 + rest // 2 * 2) * LANES].reshape(rest // 2, LANES, 2)
+        pos[full * 8 : full * 8 + rest // 2 * 2] = t.transpose(0, 2, 1).reshape(rest // 2 * 2, LANES)
+    if npos & 1:
+        pos[npos - 1] = stream[base + (npos - 1) * LANES : base + npos * LANES]
+    flags = np.zeros((npos, LANES), dtype=np.int64)
+    if npos:
+        f = stream[base + npos * LANES : base + npos * LANES + 2 * LANES].astype(np.int64).reshape(LANES, 2)
+        f0 = f[:, 0] | (f[:, 1] << 16)
+        for p_ in range(min(npos, 32)):
+            flags[p_] = (f0 >> (31 - p_)) & 1
+        if npos > 32:
+            f1 = stream[base + npos * LANES + 2 * LANES : base + npos * LANES + 3 * LANES].astype(np.int64)
+            for p_ in range(32, npos):
+                flags[p_] = (f1 >> (47 - p_)) & 1
+    return pos, flags
 
 
-def unit_groups(U, pos):
-    """(parent positions, [(header position, index positions)]) of the unit."""
-    hdr = (int(U["hdr_hi"]) << 32) | int(U["hdr_lo"])
-    npar = int(U["npar"])
-    heads = [p for p in range(int(U["npos"])) if (hdr >> p) & 1]
-    assert hdr >> int(U["npos"]) == 0 and len(heads) == int(U["ngroups"])
-    if heads:
-        assert heads[0] == npar  # the parents come first, then the first group
-    else:
-        assert npar == 0
-    return npar, [(h, list(range(h + 1, nxt))) for h, nxt in zip(heads, heads[1:] + [int(U["npos"])])]
+def unit_entries(U, pos, flags):
+    """Entries in the order the lanes own them (lane 0's run, then lane 1's ...): rows, flags, slots."""
+    rows_ = pos.T.reshape(-1)
+    fl = flags.T.reshape(-1)
+    slots = int(U["slot0"]) + np.cumsum(fl)
+    return rows_, fl, slots
 
 
 def check_streams(h, S):
@@ -186,68 +199,52 @@ def check_streams(h, S):
     assert len(blk) == info.nblocks + 1 and blk[0] == 0 and blk[-1] == len(units)
     assert np.all(np.diff(blk.astype(np.int64)) >= 1)  # every block has a unit: its outputs get written
     assert info.index_bytes + info.segment_bytes == 2 * len(stream)
-    assert info.segment_bytes == 128 * int(units["ngroups"].astype(np.int64).sum())
     assert info.work_units == len(units)
     assert info.schedule_bytes == 32 * len(units) + 4 * len(blk)
-    stored = pieces = 0
+    stored = heads = flag_bytes = 0
     next_off = 0
     for b in range(info.nblocks):
         seen = [set(), set()]
+        last_value = [-1, -1]
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
-            assert U["block"] == b and U["part"] < info.parts
+            part = int(U["part"])
+            assert U["block"] == b and part < info.parts
             assert U["units_in_block"] == blk[b + 1] - blk[b] and U["index_in_block"] == ui - blk[b]
             assert U["window"] < (1 << (k - kw))
             npos = int(U["npos"])
-            assert npos % 2 == 0 and npos <= MAX_POS and int(U["npar"]) <= MAX_OVF // LANES
-            assert int(U["stream_off"]) == next_off  # unit streams are back to back, 256-byte aligned
-            next_off += npos * LANES * 2 // ALIGN
-            pos = unit_positions(stream, U)
-            npar, groups = unit_groups(U, pos)
-            parents = pos[:npar].reshape(-1)  # parent of overflow slot x, or the null index if x is unused
-            assert np.all((parents < (1 << kw)) | (parents == rows))
-            in_use = np.flatnonzero(parents < (1 << kw)) if rows >= (1 << kw) else None
-            used_slots = []
-            nidx = 0
-            last_len = None
-            for head, idxs in groups:
-                slots = pos[head]
-                assert np.all(slots < WIN_SLOTS)
-                body = pos[idxs] if idxs else np.empty((0, LANES), dtype=np.int64)
-                assert np.all(body <= rows)  # row index or the null index
-                real = body < rows
-                lens = real.sum(axis=0)
-                # a piece may use any of its group's positions (its rows are summed); groups are ranked by
-                # descending piece length: no piece is longer than the shortest piece of the group before
-                owners = lens > 0
-                assert last_len is None or lens.max() <= last_len
-                last_len = lens[owners].min() if owners.any() else last_len
-                assert np.all(slots[~owners] >= WINDOW) and np.all(slots[~owners] < OVF_BASE)  # dummies
-                own = slots[owners]
-                assert np.all((own < (1 << kw)) | ((own >= OVF_BASE) & (own < OVF_BASE + LANES * npar)))
-                # only the unit's last group may carry one all-null position (even position count)
-                assert lens.max() >= len(idxs) - (1 if head == groups[-1][0] else 0) and lens.max() >= 1
-                used_slots += own.tolist()
-                pieces += int(owners.sum())
-                rr = body[real].tolist()
-                assert len(set(rr)) == len(rr) and not (set(rr) & seen[U["part"]])
-                seen[U["part"]] |= set(rr)
-                nidx += len(rr)
-            assert len(set(used_slots)) == len(used_slots)  # plain stores: one writer per slot and unit
-            ovf = sorted(x - OVF_BASE for x in used_slots if x >= OVF_BASE)
-            if in_use is not None:
-                assert ovf == in_use.tolist()  # exactly the overflow slots that have a parent
-            if npar:
-                assert ovf and ovf[-1] >= LANES * (npar - 1)  # no parent position without need
-            regular = set(x for x in used_slots if x < WINDOW)
-            for x in ovf:
-                par = int(parents[x])
-                assert par in regular  # a further piece follows a first piece of its segment in the same unit
-                assert (x % LANES) // 16 == par >> 7  # folded by a lane in the row of the parent's bits 7, 8
-            assert nidx == int(U["nidx"]) and len(used_slots) == int(U["npieces"])
-            stored += nidx
+            assert npos <= MAX_POS
+            assert int(U["stream_off"]) == next_off  # unit streams are back to back, 128-byte aligned
+            next_off += unit_bytes(npos) // ALIGN
+            flag_bytes += (4 * LANES if npos else 0) + (2 * LANES if npos > 32 else 0)
+            if npos == 0:
+                assert U["nentries"] == 0 and U["nrows"] == 0
+                continue
+            pos, flags = unit_positions(stream, U)
+            rr, fl, slots = unit_entries(U, pos, flags)
+            n = int(U["nentries"])
+            assert 0 < n <= npos * LANES and npos == -(-n // LANES)  # no more positions than needed
+            assert np.all(rr[n:] == rows) and np.all(fl[n:] == 0)  # the padding of the last lanes
+            assert fl[0] == 0 and rr[0] < rows and rr[n - 1] < rows  # starts and ends with a row
+            assert np.all(rr <= rows)
+            assert slots[n - 1] < (1 << kw)  # every slot lies in the window
+            real = rr[:n] < rows
+            assert np.all(fl[:n][~real] == 1)  # a null entry stands for an absent value: it always moves on
+            # consecutive real rows with the same slot ascend (equal rows stay in row order)
+            same = (slots[1:n] == slots[: n - 1]) & real[1:] & real[:-1]
+            assert np.all(rr[1:n][same] > rr[: n - 1][same])
+            values = (int(U["window"]) << kw) + slots[:n][real]
+            assert values[0] >= last_value[part]  # units of a part follow each other in value order
+            last_value[part] = int(values[-1])
+            got = rr[:n][real].tolist()
+            assert len(set(got)) == len(got) and not (set(got) & seen[part])
+            seen[part] |= set(got)
+            assert len(got) == int(U["nrows"]) and int(fl.sum()) == int(U["nheads"])
+            stored += len(got)
+            heads += int(fl.sum()) + 1
     assert next_off * ALIGN == 2 * len(stream)
-    assert stored == info.stored_rows and pieces == info.segments
+    assert stored == info.stored_rows and heads == info.segments
+    assert flag_bytes == info.segment_bytes
 
 
 @pytest.mark.parametrize("rows,cols,k,kind,seed", CASES)
@@ -258,7 +255,9 @@ def test_stream_invariants(rows, cols, k, kind, seed):
 
 
 def walk(h, S, v):
-    """numpy mirror of the kernel's traversal of the packed streams (int64 arithmetic)."""
+    """numpy mirror of the kernel's traversal of the packed streams (int64 arithmetic): every lane walks
+    its run with one running sum, stores it where a flag says that a new value starts, and what it is
+    left with is added to its last slot afterwards."""
     info = h.info
     rows, cols, k, kw = info.rows, info.cols, info.k, info.lo_bits
     units, stream, blk = S["units"], S["stream"], S["blk_unit"]
@@ -269,29 +268,23 @@ def walk(h, S, v):
         comb = np.zeros((2, 16), dtype=np.int64)
         for ui in range(blk[b], blk[b + 1]):
             U = units[ui]
-            pos = unit_positions(stream, U)
-            hdr = (int(U["hdr_hi"]) << 32) | int(U["hdr_lo"])
-            win = np.zeros(WIN_SLOTS, dtype=np.int64)
-            acc = np.zeros(LANES, dtype=np.int64)
-            slot = WINDOW + (np.arange(LANES) & (DUMMY - 1))
-            # (the kernel also gathers at the parent positions, into a dummy slot that is never read)
-            npar = int(U["npar"])
-            for p in range(npar, int(U["npos"])):
-                if (hdr >> p) & 1:
-                    win[slot] = acc
-                    slot = pos[p].copy()
-                    acc[:] = 0
-                else:
+            win = np.zeros(WINDOW, dtype=np.int64)
+            npos = int(U["npos"])
+            if npos:
+                pos, flags = unit_positions(stream, U)
+                nflag = flags.sum(axis=0)
+                slot = int(U["slot0"]) + np.cumsum(nflag) - nflag  # the lane's first slot
+                acc = np.zeros(LANES, dtype=np.int64)
+                for p in range(npos):
+                    f = flags[p].astype(bool)
+                    win[slot[f]] = acc[f]          # plain stores: one lane per slot
+                    assert len(set(slot[f].tolist())) == int(f.sum())
+                    slot = slot + flags[p]
+                    acc[f] = 0
                     acc += vl[pos[p]]
-            win[slot] = acc
-            r = win[:WINDOW] @ value_bits
-            tot = win[:WINDOW].sum()
-            parents = pos[:npar].reshape(-1)
-            for o in range(LANES * npar):
-                val = win[OVF_BASE + o]
-                if val:  # unused overflow slots stay 0 (their parent is the null index)
-                    r = r + val * value_bits[int(parents[o])]
-                    tot += val
+                np.add.at(win, slot, acc)          # the open segments
+            r = win @ value_bits
+            tot = win.sum()
             for bit in range(k):
                 t_ = r[bit] if bit < kw else (tot if (int(U["window"]) >> (bit - kw)) & 1 else 0)
                 comb[int(U["part"]), bit] += t_
@@ -310,27 +303,26 @@ def test_walk_over_packed_streams_gives_the_product(rows, cols, k, kind, seed):
     assert np.array_equal(got, dense.matvec_i8(A, v))
 
 
-def test_long_segments_are_cut_and_big_windows_split_into_units():
+def test_long_segments_and_big_windows_are_split_into_units():
     g = rng(5)
-    # 4000 rows, block width 3: seven segments of about 500 rows -> many pieces per segment
+    # 4000 rows, block width 3: seven segments of about 500 rows, each spread over many lanes
     A = g.integers(0, 2, size=(4000, 6)).astype(np.int8)
     with HostIndex(A, 3) as h:
         S = R.rsr_host_streams(h.x)
         check_streams(h, S)
-        assert S["units"]["npar"].max() > 0 and h.info.segments > 2 * 7 * 2
-        assert 2 * h.info.stored_rows > 0.75 * h.info.index_bytes  # long segments still fill the lanes
+        assert 2 * h.info.stored_rows > 0.95 * h.info.index_bytes  # long segments still fill the lanes
     # 60000 equal rows: one segment spread over several units of the same window
     A = np.ones((60000, 2), np.int8)
     with HostIndex(A, 2) as h:
         S = R.rsr_host_streams(h.x)
         check_streams(h, S)
-        assert len(S["units"]) >= 60000 // (47 * 64) and np.all(S["units"]["window"] == 0)
-        assert 2 * h.info.stored_rows > 0.9 * h.info.index_bytes
-    # short segments only: nothing is cut more than once
-    A = g.integers(0, 2, size=(1500, 9)).astype(np.int8)
-    with HostIndex(A, 9) as h:
-        S = R.rsr_host_streams(h.x)
-        assert h.info.segments < 1.5 * 511
+        assert len(S["units"]) == -(-60000 // (MAX_POS * LANES)) and np.all(S["units"]["window"] == 0)
+        assert 2 * h.info.stored_rows > 0.95 * h.info.index_bytes
+        assert S["units"]["nheads"].sum() == 0
+    # the index of a random matrix is little more than 16 bits per row plus one flag bit
+    A = g.integers(0, 2, size=(4096, 40)).astype(np.int8)
+    with HostIndex(A, 10) as h:
+        assert h.info.index_bytes + h.info.segment_bytes < 1.10 * (2 + 1 / 8) * h.info.stored_rows
 
 
 @pytest.mark.parametrize("name", ["ones", "zeros", "identity", "equal_rows", "bin_k", "two_patterns"])
@@ -362,45 +354,3 @@ def test_degenerate_matrices(name):
         if name == "bin_k":
             sigma, L = R.rsr_host_export_block(h.x, 0, 0)
             assert sigma.tolist() == list(range(1024)) and L.tolist() == list(range(1025))
-
-
-def gather_passes(S, rows):
-    """LDS passes per half-wavefront gather of float activations (bank = row mod 32): for every index
-    position and half, the largest number of distinct rows that fall into one bank."""
-    units, stream = S["units"], S["stream"]
-    total, count, worst = 0, 0, 0
-    conflict_free_possible, conflict_free = 0, 0
-    for U in units:
-        pos = unit_positions(stream, U)
-        _, groups = unit_groups(U, pos)
-        for head, idxs in groups:
-            body = pos[idxs] if idxs else np.empty((0, LANES), dtype=np.int64)
-            while body.shape[0] and np.all(body[-1] == rows):  # the position that makes the count even
-                body = body[:-1]
-            for half in (0, 1):
-                sub = body[:, 32 * half : 32 * half + 32]
-                real = sub[sub < rows]
-                degree = np.bincount(real % 32, minlength=32).max() if real.size else 0
-                passes = []
-                for t in range(sub.shape[0]):
-                    rr = np.unique(sub[t][sub[t] < rows])
-                    passes.append(max(1, int(np.bincount(rr % 32, minlength=32).max()) if rr.size else 1))
-                total += sum(passes)
-                count += len(passes)
-                worst = max(worst, max(passes, default=1))
-                if sub.shape[0] and degree <= sub.shape[0]:  # no bank has more rows than there are positions
-                    conflict_free_possible += 1
-                    conflict_free += all(x == 1 for x in passes)
-    return total / max(count, 1), worst, conflict_free_possible, conflict_free
-
-
-def test_rows_of_a_half_wavefront_are_spread_over_the_lds_banks():
-    # Random rows in random order cost about 3.5 passes per gather here.  The packer's placement must
-    # stay clearly below, must never need more than two passes where no bank holds more than twice
-    # the positions of its half group, and must be conflict-free wherever that is possible at all.
-    A = make(4096, 80, "binary", 11)
-    with HostIndex(A, 10) as h:
-        S = R.rsr_host_streams(h.x)
-        mean, worst, possible, achieved = gather_passes(S, 4096)
-    assert mean < 2.0 and worst <= 2
-    assert possible > 0 and achieved == possible
