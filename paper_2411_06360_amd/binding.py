@@ -54,16 +54,17 @@ assert UNIT_DTYPE.itemsize == 32
 
 
 def lib_path() -> str:
-    """The built library; RSR_LIB names another build of the same sources (kernel experiments)."""
-    return os.environ.get("RSR_LIB") or os.path.join(HERE, _LIB_NAME)
+    """The built library, next to this file."""
+    return os.path.join(HERE, _LIB_NAME)
 
 
-def load() -> ctypes.CDLL:
-    """Load the built library.  Never builds and never falls back to anything else."""
+def load(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load the built library (once per process; `path` names another build of the same sources and
+    only counts on the first call).  Never builds and never falls back to anything else."""
     global _lib
     if _lib is not None:
         return _lib
-    path = lib_path()
+    path = path or lib_path()
     if not os.path.exists(path):
         raise RuntimeError(
             f"{path} is missing: the HIP library has not been built "

@@ -77,8 +77,7 @@ struct rsr_handle {
   void* d_stream = nullptr;
   void* d_units = nullptr;
   void* d_blk_unit = nullptr;
-  // tuning (environment overrides read at preprocess time)
-  int waves = 16, wg_per_cu = 0;
+  int waves = 16;  // wavefronts per workgroup at most
   // host copy of the device tables, fetched on the first rsr_export_block
   std::unique_ptr<rsr::Packed> downloaded;
 };
@@ -328,6 +327,9 @@ __device__ __forceinline__ Desc load_desc(const uint32_t* __restrict__ unit_word
 }
 
 constexpr int NG = rsr::kMaxGranules;
+#ifndef RSR_HEAD_GRANULES
+#define RSR_HEAD_GRANULES 1
+#endif
 
 template <typename VT>
 __global__ void __launch_bounds__(1024)
@@ -398,11 +400,19 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     f[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(fbase + lane4), 0, kNonTemporal);
     f[1] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rs, (int)(fbase + rsr::kFlagBytes0 + lane2), 0, kNonTemporal);
   };
-  auto issue = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[4], uint32_t (&f)[2]) {
+  // A wavefront's first unit is requested in two parts: the flags and the first kHeadGranules
+  // granules before the workgroup's barrier, the rest behind it (see there).
+  constexpr int kHeadGranules = RSR_HEAD_GRANULES;
+  auto issue_head = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&f)[2]) {
     const __amdgpu_buffer_rsrc_t rs = unit_rsrc(stream_off, npos);
     issue_flags(rs, npos, f);
 #pragma unroll
-    for (int gq = 0; gq < NG; ++gq) issue_granule(rs, gq, e);
+    for (int gq = 0; gq < kHeadGranules; ++gq) issue_granule(rs, gq, e);
+  };
+  auto issue_rest = [&](uint32_t stream_off, int npos, uint32_t (&e)[NG][4], uint32_t (&et)[4]) {
+    const __amdgpu_buffer_rsrc_t rs = unit_rsrc(stream_off, npos);
+#pragma unroll
+    for (int gq = kHeadGranules; gq < NG; ++gq) issue_granule(rs, gq, e);
 #pragma unroll
     for (int j = 0; j < 3; ++j) issue_pair(rs, lane4 + (uint32_t)(npos >> 3) * 1024u, j, et);
     issue_single(rs, npos, et);
@@ -449,7 +459,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     // behind it in the queue anyway.
     const uint32_t u_first = u_begin + (uint32_t)wave;
     Desc D = load_desc(unit_words, u_first < (uint32_t)p.nunits ? u_first : 0u);
-    issue(D.stream_off, D.npos, eA, tA, fA);
+    issue_head(D.stream_off, D.npos, eA, fA);
     if (first_round) {
       // vl[rows] = 0 serves the null row index.
       uint4* l16 = reinterpret_cast<uint4*>(vl);
@@ -464,6 +474,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
       first_round = false;
     }
     __syncthreads();
+    issue_rest(D.stream_off, D.npos, eA, tA);
     int nblk = blk_end - rb0;
     if (!one_round) {
       const bool ok = (lane < p.nslot) && (rb0 + lane < blk_end) && (bu[lane + 1] - u_begin <= (uint32_t)p.ucap);
@@ -655,12 +666,6 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 // ---------------------------------------------------------------------------------------------
 // host code
 // ---------------------------------------------------------------------------------------------
-int env_int(const char* name, int dflt) {
-  const char* s = std::getenv(name);
-  if (!s || !*s) return dflt;
-  return std::atoi(s);
-}
-
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 template <typename VT>
@@ -701,7 +706,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   const int waves_fit = waves;
   const size_t ucap_fit = ucap;
   int64_t g1 = 1;
-  for (int wg = (h->wg_per_cu > 0 ? h->wg_per_cu : 4); wg >= 1; --wg) {
+  for (int wg = 4; wg >= 1; --wg) {
     g1 = ((int64_t)h->num_cu * wg + batch - 1) / batch;
     g1 = (g1 + 7) / 8 * 8;
     if (g1 > h->nblocks) g1 = h->nblocks;
@@ -715,7 +720,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
     const int64_t units_per_wg = blocks_per_wg * (int64_t)std::max<uint32_t>(1, h->max_units_per_block);
     waves = (int)std::min<int64_t>(waves_fit, units_per_wg);
     ucap = std::min<size_t>(ucap_fit, (size_t)units_per_wg);  // records for the units a workgroup can have
-    if (wg == 1 || h->wg_per_cu > 0 || (wg * waves <= 16 && (size_t)wg * total(waves, ucap) <= h->lds_max)) break;
+    if (wg == 1 || (wg * waves <= 16 && (size_t)wg * total(waves, ucap) <= h->lds_max)) break;
   }
   p.g1 = (int)g1;
   const int64_t grid = (g1 + 7) / 8 * 8 * (int64_t)batch;
@@ -772,7 +777,7 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   std::string err;
   int rc;
   try {
-    rc = rsr::pack_matrix(A, rows, cols, k, env_int("RSR_PACK_THREADS", 0), &P, &err);
+    rc = rsr::pack_matrix(A, rows, cols, k, 0, &P, &err);
   } catch (const std::bad_alloc&) {
     fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
     return nullptr;
@@ -791,10 +796,6 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   h->max_units_per_block = P.max_units_per_block;
   h->stored_rows = P.stored_rows; h->segments = P.segments; h->nunits = (int64_t)P.units.size();
   h->flag_bytes = P.flag_bytes;
-  h->waves = env_int("RSR_WAVES", 16);
-  if (h->waves < 1) h->waves = 1;
-  if (h->waves > 16) h->waves = 16;
-  h->wg_per_cu = env_int("RSR_WG_PER_CU", 0);
   // both kernels may use the whole LDS of a compute unit as dynamic shared memory
   for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float>),
                            reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>)}) {
@@ -874,7 +875,7 @@ rsr_host_index* rsr_host_pack(const int8_t* A, int64_t rows, int64_t cols, int k
   std::string err;
   int rc;
   try {
-    rc = rsr::pack_matrix(A, rows, cols, k, env_int("RSR_PACK_THREADS", 0), &x->P, &err);
+    rc = rsr::pack_matrix(A, rows, cols, k, 0, &x->P, &err);
   } catch (const std::bad_alloc&) {
     fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
     return nullptr;

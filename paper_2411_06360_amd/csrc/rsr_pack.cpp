@@ -27,6 +27,52 @@ struct Scratch {
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
+// ---- LDS banks ----
+// A gather instruction reads one activation per lane.  The LDS has 32 banks of 4 bytes and serves
+// the two halves of a wavefront (lanes 0..31, 32..63) one after the other; a half costs as many
+// cycles as its fullest bank has distinct addresses (measured on gfx950 with a stride sweep: 64 lanes
+// at stride 1, 2, 4, 8 words take 2.4, 4.1, 8.1, 16.1 cycles; two lanes of the same half on one bank
+// cost one cycle more, two lanes of different halves do not).  The bank of a float activation is
+// its row number modulo 32.  The order of the rows inside a segment is free (a segment is a sum), so
+// within every run of a lane that belongs to one segment the rows are dealt out position by position
+// in such a way that the lanes of a half meet in few banks: at each position the lanes with the
+// fewest rows left to choose from pick first, and each picks, among the rows its run still holds,
+// the one whose bank has been picked least at that position.
+constexpr int kBanks = 32;
+constexpr int kHalf = 32;
+
+void spread_over_banks(uint16_t (*ent)[kMaxPositions], const uint8_t (*flg)[kMaxPositions], int npos, uint16_t null_index) {
+  for (int h = 0; h < kLanes / kHalf; ++h) {
+    int run_end[kHalf];  // end (exclusive) of the run that covers the current position, per lane
+    for (int l = 0; l < kHalf; ++l) run_end[l] = 0;
+    for (int p = 0; p < npos; ++p) {
+      int order[kHalf], left[kHalf];
+      for (int l = 0; l < kHalf; ++l) {
+        const int L = h * kHalf + l;
+        if (run_end[l] <= p) {  // a new run starts here: up to the next flag
+          int q = p + 1;
+          while (q < npos && !flg[L][q]) ++q;
+          run_end[l] = q;
+        }
+        left[l] = run_end[l] - p;
+        order[l] = l;
+      }
+      std::stable_sort(order, order + kHalf, [&](int x, int y) { return left[x] < left[y]; });
+      int load[kBanks] = {0};
+      for (int o = 0; o < kHalf; ++o) {
+        const int l = order[o], L = h * kHalf + l;
+        int best = p;
+        for (int q = p; q < run_end[l]; ++q) {
+          if (ent[L][q] == null_index) continue;  // a null entry reads one shared word: it is placed last
+          if (ent[L][best] == null_index || load[ent[L][q] % kBanks] < load[ent[L][best] % kBanks]) best = q;
+        }
+        std::swap(ent[L][p], ent[L][best]);
+        if (ent[L][p] != null_index) ++load[ent[L][p] % kBanks];
+      }
+    }
+  }
+}
+
 // One unit: entries e[0 .. n) with their flags, the first one in window slot `slot0`.
 void emit_unit(const uint16_t* e, const uint8_t* f, int n, int slot0, uint32_t block, uint32_t window, int part,
                uint16_t null_index, BlockOut* out) {
@@ -42,8 +88,17 @@ void emit_unit(const uint16_t* e, const uint8_t* f, int n, int slot0, uint32_t b
   u.nentries = (uint32_t)n;
   if (npos > 0) {
     // entry of lane l at position p (the first entry's flag is dropped: its slot is slot0)
-    auto at = [&](int l, int p) { const int i = l * npos + p; return i < n ? e[i] : null_index; };
-    auto flag_at = [&](int l, int p) { const int i = l * npos + p; return (i > 0 && i < n) ? (int)f[i] : 0; };
+    uint16_t ent[kLanes][kMaxPositions];
+    uint8_t flg[kLanes][kMaxPositions];
+    for (int l = 0; l < kLanes; ++l)
+      for (int p = 0; p < npos; ++p) {
+        const int i = l * npos + p;
+        ent[l][p] = i < n ? e[i] : null_index;
+        flg[l][p] = (i > 0 && i < n) ? f[i] : 0;
+      }
+    spread_over_banks(ent, flg, npos, null_index);
+    auto at = [&](int l, int p) { return ent[l][p]; };
+    auto flag_at = [&](int l, int p) { return (int)flg[l][p]; };
     const int full = npos / kGranulePositions;
     for (int g = 0; g < full; ++g)
       for (int l = 0; l < kLanes; ++l)
