@@ -31,7 +31,7 @@ extern "C" {
 typedef enum rsr_status {
   RSR_OK = 0,
   RSR_ERR_INVALID_ARGUMENT = -1, /* null pointer, size out of range, entry outside {-1,0,1}, bad handle */
-  RSR_ERR_UNSUPPORTED = -2,      /* valid request this build cannot serve (e.g. rows too large for LDS) */
+  RSR_ERR_UNSUPPORTED = -2,      /* valid request this build cannot serve (an index too large for its 32-bit offsets) */
   RSR_ERR_HIP = -3,              /* a HIP runtime call failed; the message carries hipGetErrorString */
   RSR_ERR_OUT_OF_MEMORY = -4     /* host allocation failed */
 } rsr_status;
@@ -46,7 +46,11 @@ typedef struct rsr_handle rsr_handle; /* opaque; owns the device-resident index 
  *         (ternary).  The kind is inferred: any -1 makes the matrix ternary (two parts,
  *         B(1) = [A == 1] and B(2) = [A == -1]); otherwise there is one part, B = A.
  *         A is only read during the call and is not retained.
- *   rows  1 .. 65534   (row indices are stored in 16 bits; one value is reserved)
+ *   rows  1 .. 65534   (row indices are stored in 16 bits; one value is reserved).  A matrix with
+ *         more than 32768 rows is indexed as two row tiles of equal height, each with its own
+ *         permutations and segmentations; a product then takes one launch per tile and the
+ *         tiles' results add up (the product is linear in the rows).  rsr_export_block returns
+ *         the index of the whole matrix either way.
  *   cols  >= 1
  *   k     block width, 1 .. 16.  Column block i holds columns i*k .. min((i+1)*k, cols)-1
  *         (Definition 3.1); the last block may be narrower.
@@ -81,9 +85,8 @@ rsr_handle *rsr_preprocess(const int8_t *A, int64_t rows, int64_t cols, int k);
  * is reproducible from run to run; it satisfies |out - exact| <= 1e-5 * sum_i |v_i| for
  * finite inputs of ordinary magnitude.
  *
- * Errors: RSR_ERR_INVALID_ARGUMENT (null pointer, batch < 1), RSR_ERR_UNSUPPORTED (the
- * activation vector does not fit the compute unit's local memory: rows > ~38000 for float),
- * RSR_ERR_HIP (launch failure).
+ * Errors: RSR_ERR_INVALID_ARGUMENT (null pointer, batch < 1 or > 65535), RSR_ERR_HIP (launch
+ * failure).  Every row count that rsr_preprocess accepts is served.
  */
 int rsr_matvec(rsr_handle *h, const float *v, float *out, int batch, void *stream);
 
@@ -125,6 +128,8 @@ typedef struct rsr_info_t {
   int64_t table_bytes;      /* index_bytes + segment_bytes + schedule_bytes */
   int32_t device;           /* HIP device ordinal that holds the tables */
   int32_t compute_units;    /* of that device */
+  int32_t row_tiles;        /* 1, or 2 for more than 32768 rows: launches per product */
+  int32_t reserved;
 } rsr_info_t;
 
 int rsr_info(const rsr_handle *h, rsr_info_t *info); /* info: HOST pointer */
@@ -167,15 +172,18 @@ int rsr_host_info(const rsr_host_index *x, rsr_info_t *info);
 int rsr_host_export_block(const rsr_host_index *x, int part, int64_t block, int32_t *sigma, int32_t *L);
 
 /*
- * rsr_host_streams - read-only views of the packed streams exactly as they would be uploaded
- * (layout: see csrc/rsr_format.h).  Pointers are HOST memory owned by x and valid until
+ * rsr_host_streams - read-only views of the packed streams of one row tile exactly as they would
+ * be uploaded (layout: see csrc/rsr_format.h).  Pointers are HOST memory owned by x and valid until
  * rsr_host_free.  Any output pointer may be NULL.
- *   stream / n_stream     uint16 elements of the unit streams (slot ids and row indices)
+ *   tile                  0 .. row_tiles-1
+ *   stream / n_stream     uint16 elements of the unit streams (row indices, then flag words)
  *   units / n_units       32-byte unit descriptors
  *   blk_unit              nblocks + 1 uint32 offsets into units
+ *   tile_row0 / tile_rows first row and height of the tile (row indices count from tile_row0)
  */
-int rsr_host_streams(const rsr_host_index *x, const uint16_t **stream, int64_t *n_stream,
-                     const void **units, int64_t *n_units, const uint32_t **blk_unit);
+int rsr_host_streams(const rsr_host_index *x, int tile, const uint16_t **stream, int64_t *n_stream,
+                     const void **units, int64_t *n_units, const uint32_t **blk_unit,
+                     int64_t *tile_row0, int64_t *tile_rows);
 
 #ifdef __cplusplus
 }

@@ -36,6 +36,7 @@ class RsrInfo(ctypes.Structure):
         ("index_bytes", ctypes.c_int64), ("segment_bytes", ctypes.c_int64),
         ("schedule_bytes", ctypes.c_int64), ("table_bytes", ctypes.c_int64),
         ("device", ctypes.c_int32), ("compute_units", ctypes.c_int32),
+        ("row_tiles", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
     def as_dict(self) -> dict:
@@ -100,7 +101,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_host_info.restype = ci
     L.rsr_host_export_block.argtypes = [vp, ci, i64, vp, vp]
     L.rsr_host_export_block.restype = ci
-    L.rsr_host_streams.argtypes = [vp] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 2 + [ctypes.POINTER(vp)]
+    L.rsr_host_streams.argtypes = ([vp, ci] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 2 + [ctypes.POINTER(vp)]
+                                   + [ctypes.POINTER(i64)] * 2)
     L.rsr_host_streams.restype = ci
     _lib = L
     return L
@@ -201,13 +203,14 @@ def rsr_host_export_block(x: int, part: int, block: int) -> Tuple[np.ndarray, np
     return _export(load().rsr_host_export_block, x, part, block, info.rows, width)
 
 
-def rsr_host_streams(x: int) -> dict:
-    """Copies of the packed streams as numpy arrays: stream (uint16), units (structured), blk_unit."""
+def rsr_host_streams(x: int, tile: int = 0) -> dict:
+    """Copies of the packed streams of one row tile as numpy arrays: stream (uint16), units (structured),
+    blk_unit, and the tile's first row and height."""
     vp, i64 = ctypes.c_void_p, ctypes.c_int64
     pe, pu, pb = vp(), vp(), vp()
-    ne, nu = i64(), i64()
-    _check(load().rsr_host_streams(x, ctypes.byref(pe), ctypes.byref(ne), ctypes.byref(pu), ctypes.byref(nu),
-                                   ctypes.byref(pb)))
+    ne, nu, r0, nr = i64(), i64(), i64(), i64()
+    _check(load().rsr_host_streams(x, int(tile), ctypes.byref(pe), ctypes.byref(ne), ctypes.byref(pu), ctypes.byref(nu),
+                                   ctypes.byref(pb), ctypes.byref(r0), ctypes.byref(nr)))
     info = rsr_host_info(x)
 
     def view(ptr, count, dtype):
@@ -221,4 +224,6 @@ def rsr_host_streams(x: int) -> dict:
         "stream": view(pe, ne.value, np.uint16),
         "units": view(pu, nu.value, UNIT_DTYPE),
         "blk_unit": view(pb, info.nblocks + 1, np.uint32),
+        "row0": int(r0.value),
+        "rows": int(nr.value),
     }

@@ -62,6 +62,17 @@ constexpr uint64_t kMagic = 0x5253522b2b763031ull;  // "RSR++v01"
 
 }  // namespace
 
+// One row tile of the index on the device (a matrix of up to rsr::kTileRows rows has one).
+struct DeviceTile {
+  int64_t rows = 0, row0 = 0;
+  uint32_t max_units_per_block = 0;
+  int64_t nunits = 0;
+  size_t stream_bytes = 0, unit_bytes = 0, blk_bytes = 0;
+  void* d_stream = nullptr;
+  void* d_units = nullptr;
+  void* d_blk_unit = nullptr;
+};
+
 struct rsr_handle {
   uint64_t magic = 0;
   int device = 0, num_cu = 0;
@@ -69,22 +80,17 @@ struct rsr_handle {
   // shape
   int64_t rows = 0, cols = 0, nblocks = 0;
   int k = 0, kw = 0, parts = 0, last_width = 0;
-  uint32_t max_units_per_block = 0;
   int64_t stored_rows = 0, segments = 0, nunits = 0;
-  int64_t flag_bytes = 0;
-  size_t stream_bytes = 0, unit_bytes = 0, blk_bytes = 0;
-  // device tables
-  void* d_stream = nullptr;
-  void* d_units = nullptr;
-  void* d_blk_unit = nullptr;
+  int64_t flag_bytes = 0, stream_bytes = 0, schedule_bytes = 0;
+  std::vector<DeviceTile> tiles;
   int waves = 16;  // wavefronts per workgroup at most
   // host copy of the device tables, fetched on the first rsr_export_block
-  std::unique_ptr<rsr::Packed> downloaded;
+  std::unique_ptr<rsr::Index> downloaded;
 };
 
 struct rsr_host_index {
   uint64_t magic = 0;
-  rsr::Packed P;
+  rsr::Index X;
 };
 
 namespace {
@@ -93,17 +99,21 @@ constexpr uint64_t kHostMagic = 0x525352686f737431ull;  // "RSRhost1"
 
 bool valid(const rsr_host_index* x) { return x && x->magic == kHostMagic; }
 
-void fill_info(const rsr::Packed& P, rsr_info_t* info) {
+void fill_info(const rsr::Index& X, rsr_info_t* info) {
   std::memset(info, 0, sizeof(*info));
-  info->rows = P.rows; info->cols = P.cols; info->k = P.k; info->parts = P.parts;
+  const rsr::Packed& P = X.tiles[0];
+  info->rows = X.rows; info->cols = X.cols; info->k = P.k; info->parts = P.parts;
   info->nblocks = P.nblocks; info->last_block_width = P.last_width;
   info->lo_bits = P.kw; info->hi_bits = P.k - P.kw;
-  info->stored_rows = P.stored_rows; info->segments = P.segments; info->work_units = (int64_t)P.units.size();
-  info->segment_bytes = P.flag_bytes;
-  info->index_bytes = (int64_t)(P.stream.size() * sizeof(uint16_t)) - info->segment_bytes;
-  info->schedule_bytes = (int64_t)(P.units.size() * sizeof(rsr::Unit) + P.blk_unit.size() * sizeof(uint32_t));
+  for (const rsr::Packed& T : X.tiles) {
+    info->stored_rows += T.stored_rows; info->segments += T.segments; info->work_units += (int64_t)T.units.size();
+    info->segment_bytes += T.flag_bytes;
+    info->index_bytes += (int64_t)(T.stream.size() * sizeof(uint16_t)) - T.flag_bytes;
+    info->schedule_bytes += (int64_t)(T.units.size() * sizeof(rsr::Unit) + T.blk_unit.size() * sizeof(uint32_t));
+  }
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
   info->device = -1; info->compute_units = 0;
+  info->row_tiles = (int32_t)X.tiles.size();
 }
 
 bool valid(const rsr_handle* h) { return h && h->magic == kMagic; }
@@ -113,6 +123,9 @@ bool valid(const rsr_handle* h) { return h && h->magic == kMagic; }
 // ---------------------------------------------------------------------------------------------
 struct KArgs {
   int rows, cols, k, kw, parts, nblocks, last_width, batch;
+  int vstride;   // elements between the activation vectors of consecutive batch lanes (the matrix's row count)
+  int row0;      // first row of this row tile
+  int accumulate;  // add to `out` instead of overwriting it (second and later row tiles)
   int g1;        // workgroups per batch lane
   int ucap;      // unit records per round
   int nslot;     // block completion counters per round
@@ -420,7 +433,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 
   // The activation vector is staged first: its loads go out before anything else so that they do
   // not queue behind the (much larger) first stream loads of the other wavefronts.
-  const VT* __restrict__ v = vin + (int64_t)b * p.rows;
+  const VT* __restrict__ v = vin + (int64_t)b * p.vstride + p.row0;
   constexpr int per16 = 16 / (int)sizeof(VT);
   const int n16 = ((reinterpret_cast<uintptr_t>(v) & 15) == 0) ? p.rows / per16 : 0;
   const uint4* v16 = reinterpret_cast<const uint4*>(v);
@@ -647,7 +660,10 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
         // value bit `bit` belongs to column k-1-bit of the block (first column most significant)
         const int width = ((int)D.block == p.nblocks - 1) ? p.last_width : p.k;
         const int col = p.k - 1 - bit;
-        if (lane < 16 && bit < p.k && col < width) outp[(int64_t)D.block * p.k + col] = res;
+        if (lane < 16 && bit < p.k && col < width) {
+          AT* dst = outp + (int64_t)D.block * p.k + col;
+          *dst = p.accumulate ? *dst + res : res;  // row tiles add up: the product is linear in the rows
+        }
       }
       ix = ix1; D = D1;
     };
@@ -669,19 +685,15 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 template <typename VT>
-int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
-  if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
-  if (!v || !out) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer");
-  if (batch < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be >= 1");
-  if (batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be <= 65535");
-
+int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v, void* out, int batch, void* stream) {
   KArgs p;
   std::memset(&p, 0, sizeof(p));
-  p.rows = (int)h->rows; p.cols = (int)h->cols; p.k = h->k; p.kw = h->kw; p.parts = h->parts;
+  p.rows = (int)T.rows; p.cols = (int)h->cols; p.k = h->k; p.kw = h->kw; p.parts = h->parts;
   p.nblocks = (int)h->nblocks; p.last_width = h->last_width; p.batch = batch;
+  p.vstride = (int)h->rows; p.row0 = (int)T.row0; p.accumulate = accumulate ? 1 : 0;
 
   // LDS budget: activation vector + per-wavefront windows + unit records + counters
-  const size_t vbytes = align_up(((size_t)h->rows + 1) * sizeof(VT), 16);
+  const size_t vbytes = align_up(((size_t)T.rows + 1) * sizeof(VT), 16);
   const size_t win_bytes = (size_t)rsr::kWindow * 4;
   const size_t rec_bytes = (size_t)rsr::kRecordWords * 4;
   int nslot = 64;
@@ -691,14 +703,14 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   int waves = 0;
   auto total = [&](int w, size_t uc) { return vbytes + (size_t)w * win_bytes + uc * rec_bytes + (size_t)nslot * 4 + 16 + ((size_t)nslot + 1) * 4 + 12; };
   for (size_t cand : {(size_t)512, (size_t)256, (size_t)128, (size_t)64, (size_t)1}) {
-    const size_t uc = std::max<size_t>(h->max_units_per_block, cand);
+    const size_t uc = std::max<size_t>(T.max_units_per_block, cand);
     int w = h->waves;
     while (w > 1 && total(w, uc) > h->lds_max) --w;
     if (total(w, uc) <= h->lds_max && w > waves) { waves = w; ucap = uc; }
   }
   if (waves == 0)
-    return fail(RSR_ERR_UNSUPPORTED, "activation vector of " + std::to_string(h->rows) + " rows does not fit in " +
-                                         std::to_string(h->lds_max) + " bytes of LDS");
+    return fail(RSR_ERR_UNSUPPORTED, "a row tile of " + std::to_string(T.rows) + " rows with " + std::to_string(T.max_units_per_block) +
+                                         " work units in a column block does not fit in " + std::to_string(h->lds_max) + " bytes of LDS");
   // Grid and workgroup size.  Up to four workgroups per compute unit if they fit together (LDS, and 16
   // wavefronts per compute unit at this kernel's register count); never more workgroups than blocks; and
   // no more wavefronts than the largest share of a workgroup has units: idle wavefronts only lengthen
@@ -717,7 +729,7 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
     // stay idle, and the product is 0.5 us faster: the stream is shared by all compute units and the
     // workgroups with the larger share finish last either way, only later when more of them compete.)
     g1 = (h->nblocks + blocks_per_wg - 1) / blocks_per_wg;
-    const int64_t units_per_wg = blocks_per_wg * (int64_t)std::max<uint32_t>(1, h->max_units_per_block);
+    const int64_t units_per_wg = blocks_per_wg * (int64_t)std::max<uint32_t>(1, T.max_units_per_block);
     waves = (int)std::min<int64_t>(waves_fit, units_per_wg);
     ucap = std::min<size_t>(ucap_fit, (size_t)units_per_wg);  // records for the units a workgroup can have
     if (wg == 1 || (wg * waves <= 16 && (size_t)wg * total(waves, ucap) <= h->lds_max)) break;
@@ -733,34 +745,50 @@ int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
   p.off_done = (uint32_t)(p.off_rec + ucap * rec_bytes);
   p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
   p.off_bu = p.off_ctr + 16;
-  p.nunits = (int)h->nunits;
+  p.nunits = (int)T.nunits;
 
   auto kern = rsr_matvec_kernel<VT>;
   hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream),
-                     static_cast<const unsigned char*>(h->d_stream), static_cast<const uint32_t*>(h->d_units), static_cast<const uint32_t*>(h->d_blk_unit), v,
+                     static_cast<const unsigned char*>(T.d_stream), static_cast<const uint32_t*>(T.d_units), static_cast<const uint32_t*>(T.d_blk_unit), v,
                      static_cast<typename Acc<VT>::type*>(out), p);
   RSR_HIP_TRY(hipGetLastError());
   return RSR_OK;
 }
 
-void free_tables(rsr_handle* h) {
-  if (h->d_stream) (void)hipFree(h->d_stream);
-  if (h->d_units) (void)hipFree(h->d_units);
-  if (h->d_blk_unit) (void)hipFree(h->d_blk_unit);
-  h->d_stream = h->d_units = h->d_blk_unit = nullptr;
+// One launch per row tile, in order, on the caller's stream: the first overwrites `out`, the others add.
+template <typename VT>
+int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
+  if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
+  if (!v || !out) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer");
+  if (batch < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be >= 1");
+  if (batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be <= 65535");
+  for (size_t t = 0; t < h->tiles.size(); ++t) {
+    const int rc = launch_tile<VT>(h, h->tiles[t], t > 0, v, out, batch, stream);
+    if (rc != RSR_OK) return rc;
+  }
+  return RSR_OK;
 }
 
-int upload(rsr_handle* h, const rsr::Packed& P) {
-  h->stream_bytes = P.stream.size() * sizeof(uint16_t);
-  h->unit_bytes = P.units.size() * sizeof(rsr::Unit);
-  h->blk_bytes = P.blk_unit.size() * sizeof(uint32_t);
-  RSR_HIP_TRY(hipMalloc(&h->d_stream, h->stream_bytes + 1024));
-  RSR_HIP_TRY(hipMalloc(&h->d_units, h->unit_bytes + 32));
-  RSR_HIP_TRY(hipMalloc(&h->d_blk_unit, h->blk_bytes + 16));
-  RSR_HIP_TRY(hipMemset(static_cast<unsigned char*>(h->d_stream) + h->stream_bytes, 0, 1024));
-  if (h->stream_bytes) RSR_HIP_TRY(hipMemcpy(h->d_stream, P.stream.data(), h->stream_bytes, hipMemcpyHostToDevice));
-  if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(h->d_units, P.units.data(), h->unit_bytes, hipMemcpyHostToDevice));
-  RSR_HIP_TRY(hipMemcpy(h->d_blk_unit, P.blk_unit.data(), h->blk_bytes, hipMemcpyHostToDevice));
+void free_tables(rsr_handle* h) {
+  for (DeviceTile& T : h->tiles) {
+    if (T.d_stream) (void)hipFree(T.d_stream);
+    if (T.d_units) (void)hipFree(T.d_units);
+    if (T.d_blk_unit) (void)hipFree(T.d_blk_unit);
+    T.d_stream = T.d_units = T.d_blk_unit = nullptr;
+  }
+}
+
+int upload(DeviceTile* T, const rsr::Packed& P) {
+  T->stream_bytes = P.stream.size() * sizeof(uint16_t);
+  T->unit_bytes = P.units.size() * sizeof(rsr::Unit);
+  T->blk_bytes = P.blk_unit.size() * sizeof(uint32_t);
+  RSR_HIP_TRY(hipMalloc(&T->d_stream, T->stream_bytes + 1024));
+  RSR_HIP_TRY(hipMalloc(&T->d_units, T->unit_bytes + 32));
+  RSR_HIP_TRY(hipMalloc(&T->d_blk_unit, T->blk_bytes + 16));
+  RSR_HIP_TRY(hipMemset(static_cast<unsigned char*>(T->d_stream) + T->stream_bytes, 0, 1024));
+  if (T->stream_bytes) RSR_HIP_TRY(hipMemcpy(T->d_stream, P.stream.data(), T->stream_bytes, hipMemcpyHostToDevice));
+  if (T->unit_bytes) RSR_HIP_TRY(hipMemcpy(T->d_units, P.units.data(), T->unit_bytes, hipMemcpyHostToDevice));
+  RSR_HIP_TRY(hipMemcpy(T->d_blk_unit, P.blk_unit.data(), T->blk_bytes, hipMemcpyHostToDevice));
   RSR_HIP_TRY(hipDeviceSynchronize());
   return RSR_OK;
 }
@@ -773,11 +801,11 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   g_error.clear();
   std::unique_ptr<rsr_handle> h(new (std::nothrow) rsr_handle());
   if (!h) { fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory"); return nullptr; }
-  rsr::Packed P;
+  rsr::Index X;
   std::string err;
   int rc;
   try {
-    rc = rsr::pack_matrix(A, rows, cols, k, 0, &P, &err);
+    rc = rsr::pack_tiles(A, rows, cols, k, 0, &X, &err);
   } catch (const std::bad_alloc&) {
     fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
     return nullptr;
@@ -791,18 +819,26 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipGetDeviceProperties: ") + hipGetErrorString(e)); return nullptr; }
   h->num_cu = prop.multiProcessorCount;
   h->lds_max = prop.sharedMemPerBlock;
-  h->rows = P.rows; h->cols = P.cols; h->nblocks = P.nblocks;
-  h->k = P.k; h->kw = P.kw; h->parts = P.parts; h->last_width = P.last_width;
-  h->max_units_per_block = P.max_units_per_block;
-  h->stored_rows = P.stored_rows; h->segments = P.segments; h->nunits = (int64_t)P.units.size();
-  h->flag_bytes = P.flag_bytes;
+  rsr_info_t info;
+  fill_info(X, &info);
+  h->rows = rows; h->cols = cols; h->nblocks = info.nblocks;
+  h->k = info.k; h->kw = info.lo_bits; h->parts = info.parts; h->last_width = info.last_block_width;
+  h->stored_rows = info.stored_rows; h->segments = info.segments; h->nunits = info.work_units;
+  h->flag_bytes = info.segment_bytes; h->stream_bytes = info.index_bytes + info.segment_bytes; h->schedule_bytes = info.schedule_bytes;
   // both kernels may use the whole LDS of a compute unit as dynamic shared memory
   for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float>),
                            reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>)}) {
     e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_max);
     if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e)); return nullptr; }
   }
-  if (upload(h.get(), P) != RSR_OK) { free_tables(h.get()); return nullptr; }
+  h->tiles.resize(X.tiles.size());
+  for (size_t t = 0; t < X.tiles.size(); ++t) {
+    DeviceTile& T = h->tiles[t];
+    T.rows = X.tiles[t].rows; T.row0 = X.row0[t];
+    T.max_units_per_block = X.tiles[t].max_units_per_block;
+    T.nunits = (int64_t)X.tiles[t].units.size();
+    if (upload(&T, X.tiles[t]) != RSR_OK) { free_tables(h.get()); return nullptr; }
+  }
   h->magic = kMagic;
   return h.release();
 }
@@ -832,35 +868,44 @@ int rsr_info(const rsr_handle* h, rsr_info_t* info) {
   info->lo_bits = h->kw; info->hi_bits = h->k - h->kw;
   info->stored_rows = h->stored_rows; info->segments = h->segments; info->work_units = h->nunits;
   info->segment_bytes = h->flag_bytes;
-  info->index_bytes = (int64_t)h->stream_bytes - info->segment_bytes;
-  info->schedule_bytes = (int64_t)(h->unit_bytes + h->blk_bytes);
+  info->index_bytes = h->stream_bytes - h->flag_bytes;
+  info->schedule_bytes = h->schedule_bytes;
   info->table_bytes = info->index_bytes + info->segment_bytes + info->schedule_bytes;
   info->device = h->device; info->compute_units = h->num_cu;
+  info->row_tiles = (int32_t)h->tiles.size();
   return RSR_OK;
 }
 
 int rsr_export_block(rsr_handle* h, int part, int64_t block, int32_t* sigma, int32_t* L) {
   if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
   if (!h->downloaded) {
-    std::unique_ptr<rsr::Packed> P(new (std::nothrow) rsr::Packed());
-    if (!P) return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
-    try {
-      P->stream.resize(h->stream_bytes / sizeof(uint16_t));
-      P->units.resize(h->unit_bytes / sizeof(rsr::Unit));
-      P->blk_unit.resize(h->blk_bytes / sizeof(uint32_t));
-    } catch (const std::bad_alloc&) {
-      return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
-    }
-    P->rows = h->rows; P->cols = h->cols; P->k = h->k; P->kw = h->kw; P->parts = h->parts;
-    P->nblocks = h->nblocks; P->last_width = h->last_width;
+    std::unique_ptr<rsr::Index> X(new (std::nothrow) rsr::Index());
+    if (!X) return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
     int dev = 0;
     RSR_HIP_TRY(hipGetDevice(&dev));
     RSR_HIP_TRY(hipSetDevice(h->device));
-    if (h->stream_bytes) RSR_HIP_TRY(hipMemcpy(P->stream.data(), h->d_stream, h->stream_bytes, hipMemcpyDeviceToHost));
-    if (h->unit_bytes) RSR_HIP_TRY(hipMemcpy(P->units.data(), h->d_units, h->unit_bytes, hipMemcpyDeviceToHost));
-    RSR_HIP_TRY(hipMemcpy(P->blk_unit.data(), h->d_blk_unit, h->blk_bytes, hipMemcpyDeviceToHost));
+    X->rows = h->rows; X->cols = h->cols;
+    try {
+      X->tiles.resize(h->tiles.size());
+      for (size_t t = 0; t < h->tiles.size(); ++t) {
+        const DeviceTile& T = h->tiles[t];
+        rsr::Packed& P = X->tiles[t];
+        X->row0.push_back(T.row0);
+        P.stream.resize(T.stream_bytes / sizeof(uint16_t));
+        P.units.resize(T.unit_bytes / sizeof(rsr::Unit));
+        P.blk_unit.resize(T.blk_bytes / sizeof(uint32_t));
+        P.rows = T.rows; P.cols = h->cols; P.k = h->k; P.kw = h->kw; P.parts = h->parts;
+        P.nblocks = h->nblocks; P.last_width = h->last_width;
+        if (T.stream_bytes) RSR_HIP_TRY(hipMemcpy(P.stream.data(), T.d_stream, T.stream_bytes, hipMemcpyDeviceToHost));
+        if (T.unit_bytes) RSR_HIP_TRY(hipMemcpy(P.units.data(), T.d_units, T.unit_bytes, hipMemcpyDeviceToHost));
+        RSR_HIP_TRY(hipMemcpy(P.blk_unit.data(), T.d_blk_unit, T.blk_bytes, hipMemcpyDeviceToHost));
+      }
+    } catch (const std::bad_alloc&) {
+      (void)hipSetDevice(dev);
+      return fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory");
+    }
     RSR_HIP_TRY(hipSetDevice(dev));
-    h->downloaded = std::move(P);
+    h->downloaded = std::move(X);
   }
   std::string err;
   const int rc = rsr::decode_block(*h->downloaded, part, block, sigma, L, &err);
@@ -875,7 +920,7 @@ rsr_host_index* rsr_host_pack(const int8_t* A, int64_t rows, int64_t cols, int k
   std::string err;
   int rc;
   try {
-    rc = rsr::pack_matrix(A, rows, cols, k, 0, &x->P, &err);
+    rc = rsr::pack_tiles(A, rows, cols, k, 0, &x->X, &err);
   } catch (const std::bad_alloc&) {
     fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory while packing");
     return nullptr;
@@ -893,26 +938,30 @@ void rsr_host_free(rsr_host_index* x) {
 
 int rsr_host_info(const rsr_host_index* x, rsr_info_t* info) {
   if (!valid(x) || !info) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index or null info");
-  fill_info(x->P, info);
+  fill_info(x->X, info);
   return RSR_OK;
 }
 
 int rsr_host_export_block(const rsr_host_index* x, int part, int64_t block, int32_t* sigma, int32_t* L) {
   if (!valid(x)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index");
   std::string err;
-  const int rc = rsr::decode_block(x->P, part, block, sigma, L, &err);
+  const int rc = rsr::decode_block(x->X, part, block, sigma, L, &err);
   if (rc != 0) return fail(rc, "rsr_host_export_block: " + err);
   return RSR_OK;
 }
 
-int rsr_host_streams(const rsr_host_index* x, const uint16_t** stream, int64_t* n_stream, const void** units,
-                     int64_t* n_units, const uint32_t** blk_unit) {
+int rsr_host_streams(const rsr_host_index* x, int tile, const uint16_t** stream, int64_t* n_stream, const void** units,
+                     int64_t* n_units, const uint32_t** blk_unit, int64_t* tile_row0, int64_t* tile_rows) {
   if (!valid(x)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid host index");
-  if (stream) *stream = x->P.stream.data();
-  if (n_stream) *n_stream = (int64_t)x->P.stream.size();
-  if (units) *units = x->P.units.data();
-  if (n_units) *n_units = (int64_t)x->P.units.size();
-  if (blk_unit) *blk_unit = x->P.blk_unit.data();
+  if (tile < 0 || tile >= (int)x->X.tiles.size()) return fail(RSR_ERR_INVALID_ARGUMENT, "row tile out of range");
+  const rsr::Packed& P = x->X.tiles[(size_t)tile];
+  if (stream) *stream = P.stream.data();
+  if (n_stream) *n_stream = (int64_t)P.stream.size();
+  if (units) *units = P.units.data();
+  if (n_units) *n_units = (int64_t)P.units.size();
+  if (blk_unit) *blk_unit = P.blk_unit.data();
+  if (tile_row0) *tile_row0 = x->X.row0[(size_t)tile];
+  if (tile_rows) *tile_rows = P.rows;
   return RSR_OK;
 }
 

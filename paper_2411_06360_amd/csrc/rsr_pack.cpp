@@ -223,7 +223,7 @@ void pack_block(int64_t rows, int k, int kw, int parts, int64_t block, Scratch* 
 
 }  // namespace
 
-int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, Packed* out, std::string* err) {
+int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, int force_parts, Packed* out, std::string* err) {
   if (!A || !out) { *err = "null pointer"; return -1; }
   if (rows < 1 || rows > kMaxRows) { *err = "rows must be in 1..65534"; return -1; }
   if (cols < 1) { *err = "cols must be >= 1"; return -1; }
@@ -266,7 +266,7 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
     *err = "entry outside {-1,0,1} at row " + std::to_string(i / cols) + ", column " + std::to_string(i % cols);
     return -1;
   }
-  const int parts = any_minus.load() ? 2 : 1;
+  const int parts = force_parts ? force_parts : (any_minus.load() ? 2 : 1);
   const int kw = std::min(k, kMaxWindowBits);
 
   std::vector<BlockOut> blocks((size_t)nblocks);
@@ -354,35 +354,69 @@ static inline int flag_at(const uint16_t* us, int npos, int p, int l) {
   return (int)((f1[l] >> (47 - p)) & 1u);
 }
 
-int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32_t* L, std::string* err) {
-  if (part < 0 || part >= P.parts) { *err = "part out of range"; return -1; }
-  if (block < 0 || block >= P.nblocks) { *err = "block out of range"; return -1; }
-  const int width = (block == P.nblocks - 1) ? P.last_width : P.k;
-  const int shift = P.k - width;
-  const uint32_t nvals = 1u << width;
-  const uint16_t null_index = (uint16_t)P.rows;
-  std::vector<std::vector<int32_t>> by_value(nvals);
-  std::vector<uint8_t> listed((size_t)P.rows, 0);
-  for (uint32_t ui = P.blk_unit[(size_t)block]; ui < P.blk_unit[(size_t)block + 1]; ++ui) {
-    const Unit& u = P.units[ui];
-    if (u.part != part) continue;
-    if (u.npos > kMaxPositions) { *err = "corrupt unit: position count"; return -1; }
-    const uint16_t* us = &P.stream[(size_t)u.stream_off * (kStreamAlign / sizeof(uint16_t))];
-    uint32_t sl = u.slot0;
-    for (int l = 0; l < kLanes; ++l)
-      for (int p = 0; p < u.npos; ++p) {
-        sl += (uint32_t)flag_at(us, u.npos, p, l);
-        const uint16_t row = stream_at(us, u.npos, p, l);
-        if (row == null_index) continue;
-        if (row > null_index) { *err = "corrupt unit: row index out of range"; return -1; }
-        if (sl >= (1u << P.kw)) { *err = "corrupt unit: slot outside the window"; return -1; }
-        const uint32_t value = (((uint32_t)u.window << P.kw) + sl) >> shift;
-        if (value >= nvals || value == 0 || listed[row]) { *err = "corrupt unit: bad value or repeated row"; return -1; }
-        listed[row] = 1;
-        by_value[value].push_back((int32_t)row);
-      }
+int pack_tiles(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, Index* out, std::string* err) {
+  if (!A || !out) { *err = "null pointer"; return -1; }
+  if (rows < 1 || rows > kMaxRows) { *err = "rows must be in 1..65534"; return -1; }
+  if (cols < 1) { *err = "cols must be >= 1"; return -1; }
+  out->rows = rows; out->cols = cols;
+  out->tiles.clear(); out->row0.clear();
+  const int64_t ntiles = (rows + kTileRows - 1) / kTileRows;
+  // equal heights, multiples of 16 rows (a tile's share of an activation vector stays 16-byte aligned)
+  const int64_t height = ((rows + ntiles - 1) / ntiles + 15) / 16 * 16;
+  int parts = 0;
+  if (ntiles > 1) {  // the kind is a property of the whole matrix
+    parts = 1;
+    for (int64_t i = 0; i < rows * cols; ++i)
+      if (A[i] < 0) { parts = 2; break; }
   }
-  for (int64_t r = 0; r < P.rows; ++r)
+  for (int64_t t = 0; t < ntiles; ++t) {
+    const int64_t r0 = t * height, r1 = std::min(rows, r0 + height);
+    out->tiles.emplace_back();
+    out->row0.push_back(r0);
+    const int rc = pack_matrix(A + r0 * cols, r1 - r0, cols, k, threads, parts, &out->tiles.back(), err);
+    if (rc != 0) {
+      // (positions in the message count from the tile's first row)
+      if (ntiles > 1) *err += " (rows counted from row " + std::to_string(r0) + ")";
+      return rc;
+    }
+  }
+  return 0;
+}
+
+int decode_block(const Index& X, int part, int64_t block, int32_t* sigma, int32_t* L, std::string* err) {
+  const Packed& P0 = X.tiles[0];
+  if (part < 0 || part >= P0.parts) { *err = "part out of range"; return -1; }
+  if (block < 0 || block >= P0.nblocks) { *err = "block out of range"; return -1; }
+  const int width = (block == P0.nblocks - 1) ? P0.last_width : P0.k;
+  const int shift = P0.k - width;
+  const uint32_t nvals = 1u << width;
+  std::vector<std::vector<int32_t>> by_value(nvals);
+  std::vector<uint8_t> listed((size_t)X.rows, 0);
+  for (size_t t = 0; t < X.tiles.size(); ++t) {
+    const Packed& P = X.tiles[t];
+    const int64_t r0 = X.row0[t];
+    const uint16_t null_index = (uint16_t)P.rows;
+    for (uint32_t ui = P.blk_unit[(size_t)block]; ui < P.blk_unit[(size_t)block + 1]; ++ui) {
+      const Unit& u = P.units[ui];
+      if (u.part != part) continue;
+      if (u.npos > kMaxPositions) { *err = "corrupt unit: position count"; return -1; }
+      const uint16_t* us = &P.stream[(size_t)u.stream_off * (kStreamAlign / sizeof(uint16_t))];
+      uint32_t sl = u.slot0;
+      for (int l = 0; l < kLanes; ++l)
+        for (int p = 0; p < u.npos; ++p) {
+          sl += (uint32_t)flag_at(us, u.npos, p, l);
+          const uint16_t row = stream_at(us, u.npos, p, l);
+          if (row == null_index) continue;
+          if (row > null_index) { *err = "corrupt unit: row index out of range"; return -1; }
+          if (sl >= (1u << P.kw)) { *err = "corrupt unit: slot outside the window"; return -1; }
+          const uint32_t value = (((uint32_t)u.window << P.kw) + sl) >> shift;
+          if (value >= nvals || value == 0 || listed[(size_t)(r0 + row)]) { *err = "corrupt unit: bad value or repeated row"; return -1; }
+          listed[(size_t)(r0 + row)] = 1;
+          by_value[value].push_back((int32_t)(r0 + row));
+        }
+    }
+  }
+  for (int64_t r = 0; r < X.rows; ++r)
     if (!listed[(size_t)r]) by_value[0].push_back((int32_t)r);  // the rows that were left out have value 0
   int64_t p = 0;
   for (uint32_t j = 0; j < nvals; ++j) {

@@ -27,11 +27,23 @@ struct Packed {
 
 // Builds the packed index of A (row-major rows x cols, entries in {-1,0,1}).  Returns 0 or a
 // negative rsr_status value; *err describes the failure.  `threads` <= 0 picks a default.
-int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, Packed* out, std::string* err);
+// `parts` = 0 infers the kind (any -1 makes the matrix ternary), 1 or 2 forces it (2 for a tile of
+// a ternary matrix that happens to hold no -1).
+int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, int parts, Packed* out, std::string* err);
 
-// Recovers sigma (rows entries) and L (2^width + 1 entries) of one block from a packed index.
+// A matrix with more rows than kTileRows is indexed in row tiles of equal height (the product
+// is linear in the rows: the tiles' products add up).  Every tile is a packed index of its own.
+constexpr int64_t kTileRows = 32768;
+struct Index {
+  int64_t rows = 0, cols = 0;
+  std::vector<Packed> tiles;
+  std::vector<int64_t> row0;   // first row of every tile
+};
+int pack_tiles(const int8_t* A, int64_t rows, int64_t cols, int k, int threads, Index* out, std::string* err);
+
+// Recovers sigma (rows entries) and L (2^width + 1 entries) of one block from the packed tiles.
 // Either output pointer may be null.
-int decode_block(const Packed& P, int part, int64_t block, int32_t* sigma, int32_t* L, std::string* err);
+int decode_block(const Index& X, int part, int64_t block, int32_t* sigma, int32_t* L, std::string* err);
 
 }  // namespace rsr
 #endif  // RSR_PACK_H_

@@ -107,11 +107,43 @@ def test_layout_paths(name, rows, cols, k, what):
         if name == "equal_rows":  # closed form: every output is the sum of v
             v1 = np.ones((1, rows), np.int8)
             assert np.all(d.matvec(v1) == rows)
-    if name == "equal_rows":  # the int8 path takes twice the rows (a float vector of 60000 does not fit the LDS)
+    if name == "equal_rows":  # and twice the rows: one segment over two row tiles
         A2 = np.ones((60000, 2), np.int8)
         with DeviceIndex(A2, 2) as d:
             v8 = g.integers(-127, 128, size=(1, 60000), dtype=np.int8)
             assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A2, v8))
+            vf = (g.random((1, 60000)) + 0.5).astype(np.float32)
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A2, vf), vf)
+
+
+def test_extreme_activations_int8_minus_128_and_coherent_float_signs():
+    """Where the stated bounds are actually exercised: int8 activations all at -128 on a matrix whose
+    rows all count (|sum| = 128 * rows, the largest magnitude the int32 accumulator sees), and float
+    activations that are all positive on 30000 equal rows (every output is the sum of the whole vector,
+    so rounding errors cannot cancel: the error bound 1e-5 * sum|v| is checked element by element)."""
+    g = rng(61)
+    rows = 30000
+    A = np.ones((rows, 6), np.int8)
+    A[:, 3:] = -1
+    note("extremes: 30000 equal rows, int8 -128 and all-positive float")
+    with DeviceIndex(A, 3) as d:
+        v8 = np.full((2, rows), -128, np.int8)
+        v8[1, ::2] = 127
+        got = d.matvec(v8).astype(np.int64)
+        assert np.array_equal(got, dense.matvec_i8(A, v8))
+        assert got[0, 0] == -128 * rows and got[0, 5] == 128 * rows
+        vf = (g.random((2, rows)) + 0.5).astype(np.float32)          # all in [0.5, 1.5)
+        vf[1] *= np.float32(1000.0)
+        worst = assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+        note(f"  coherent signs: worst error / bound = {worst:.3g}")
+    # the same on random binary rows with 16 rows per segment on average and all-positive activations
+    B = g.integers(0, 2, size=(rows, 44)).astype(np.int8)
+    with DeviceIndex(B, 11) as d:
+        vf = (g.random((1, rows)) + 0.5).astype(np.float32)
+        worst = assert_f32_close(d.matvec(vf), dense.matvec_f32(B, vf), vf)
+        note(f"  random rows, positive activations: worst error / bound = {worst:.3g}")
+        v8 = np.full((1, rows), -128, np.int8)
+        assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(B, v8))
 
 
 def test_k_invariance_same_matrix_every_k():
@@ -250,23 +282,44 @@ def test_unaligned_activation_pointer_and_odd_row_count():
         assert_f32_close(out.cpu().numpy(), dense.matvec_f32(A, vf[0]), vf[0])
 
 
+def test_more_than_32768_rows_two_row_tiles_float_and_int8():
+    """Matrices above 32768 rows are indexed in two row tiles (one launch each, results add up): the float
+    path serves every row count the index accepts, and the exported tables are those of the whole matrix."""
+    g = rng(67)
+    for rows, cols, k in [(41000, 24, 4), (60000, 33, 11), (65534, 5, 5)]:
+        A = g.integers(-1, 2, size=(rows, cols)).astype(np.int8)
+        note(f"row tiles {rows}x{cols} k={k}")
+        with DeviceIndex(A, k) as d:
+            assert d.info.row_tiles == 2
+            for batch in (1, 3):
+                vf = g.standard_normal((batch, rows)).astype(np.float32)
+                assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+                v8 = g.integers(-127, 128, size=(batch, rows), dtype=np.int8)
+                assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+            if cols < 10:
+                for p_, Bp in enumerate(steps.ternary_split(A)):
+                    sigma, L = R.rsr_export_block(d.handle, p_, 0)
+                    Bi = steps.column_blocks(Bp, k)[0]
+                    assert np.array_equal(sigma, steps.binary_row_order(Bi))
+                    assert np.array_equal(L[:-1], steps.full_segmentation(Bi))
+
+
 def test_errors_from_the_device_entry_points():
     import torch
 
-    A = np.zeros((41000, 8), np.int8)
+    A = np.zeros((300, 8), np.int8)
     A[::2] = 1
-    with DeviceIndex(A, 4) as d:  # float vector of 41000 rows (164 KB) cannot sit in LDS; int8 can
-        v = torch.zeros(41000, dtype=torch.float32, device="cuda")
+    with DeviceIndex(A, 4) as d:
+        v = torch.zeros(300, dtype=torch.float32, device="cuda")
         out = torch.zeros(8, dtype=torch.float32, device="cuda")
-        with pytest.raises(R.RsrError) as e:
-            R.rsr_matvec(d.handle, v, out, 1, None)
-        assert e.value.code == -2
-        v8 = np.ones(41000, np.int8)
-        assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
         with pytest.raises(R.RsrError):
             R.rsr_matvec(d.handle, v, out, 0, None)
         with pytest.raises(R.RsrError):
             R.rsr_matvec(d.handle, None, out, 1, None)
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec(d.handle, v, out, 70000, None)
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec_i8(d.handle, v, None, 1, None)
 
 
 # ---- the big configurations, in full ----------------------------------------------------------------------

@@ -112,7 +112,8 @@ CASES = [
     (700, 26, 13, "ternary", 5),    # ragged last block of width 13 -> exactly 2 blocks
     (100, 33, 16, "ternary", 6),    # widest k, ragged last block of width 1
     (40, 7, 1, "ternary", 7),
-    (2000, 20, 5, "binary", 8),     # long segments (about 62 rows): several pieces each
+    (2000, 20, 5, "binary", 8),     # long segments (about 62 rows): spread over many lanes
+    (40000, 7, 3, "ternary", 9),    # more than 32768 rows: two row tiles
 ]
 
 
@@ -190,17 +191,28 @@ def unit_entries(U, pos, flags):
     return rows_, fl, slots
 
 
-def check_streams(h, S):
+def check_streams(h, S=None):
+    """Invariants of the packed streams, over all row tiles (S: the streams of tile 0 if already fetched)."""
     info = h.info
-    rows, k, kw = info.rows, info.k, info.lo_bits
+    tiles = [S if (S is not None and t == 0) else R.rsr_host_streams(h.x, t) for t in range(info.row_tiles)]
+    assert info.row_tiles == max(1, -(-info.rows // 32768))
+    assert sum(T["rows"] for T in tiles) == info.rows and tiles[0]["row0"] == 0
+    assert all(a["row0"] + a["rows"] == b["row0"] for a, b in zip(tiles, tiles[1:]))
+    assert info.index_bytes + info.segment_bytes == sum(2 * len(T["stream"]) for T in tiles)
+    assert info.work_units == sum(len(T["units"]) for T in tiles)
+    assert info.schedule_bytes == sum(32 * len(T["units"]) + 4 * len(T["blk_unit"]) for T in tiles)
+    totals = [check_tile(info, T) for T in tiles]
+    assert sum(t[0] for t in totals) == info.stored_rows and sum(t[1] for t in totals) == info.segments
+    assert sum(t[2] for t in totals) == info.segment_bytes
+
+
+def check_tile(info, S):
+    rows, k, kw = S["rows"], info.k, info.lo_bits
     units, stream, blk = S["units"], S["stream"], S["blk_unit"]
     assert kw == min(k, 9)
     assert len(stream) % (ALIGN // 2) == 0
     assert len(blk) == info.nblocks + 1 and blk[0] == 0 and blk[-1] == len(units)
     assert np.all(np.diff(blk.astype(np.int64)) >= 1)  # every block has a unit: its outputs get written
-    assert info.index_bytes + info.segment_bytes == 2 * len(stream)
-    assert info.work_units == len(units)
-    assert info.schedule_bytes == 32 * len(units) + 4 * len(blk)
     stored = heads = flag_bytes = 0
     next_off = 0
     for b in range(info.nblocks):
@@ -241,8 +253,7 @@ def check_streams(h, S):
             stored += len(got)
             heads += int(fl.sum()) + 1
     assert next_off * ALIGN == 2 * len(stream)
-    assert stored == info.stored_rows and heads == info.segments
-    assert flag_bytes == info.segment_bytes
+    return stored, heads, flag_bytes
 
 
 @pytest.mark.parametrize("rows,cols,k,kind,seed", CASES)
@@ -255,9 +266,17 @@ def test_stream_invariants(rows, cols, k, kind, seed):
 def walk(h, S, v):
     """numpy mirror of the kernel's traversal of the packed streams (int64 arithmetic): every lane walks
     its run with one running sum, stores it where a flag says that a new value starts, and what it is
-    left with is added to its last slot afterwards."""
+    left with is added to its last slot afterwards.  The products of the row tiles add up."""
     info = h.info
-    rows, cols, k, kw = info.rows, info.cols, info.k, info.lo_bits
+    out = np.zeros(info.cols, dtype=np.int64)
+    for t in range(info.row_tiles):
+        T = S if t == 0 else R.rsr_host_streams(h.x, t)
+        out += walk_tile(info, T, np.asarray(v)[T["row0"] : T["row0"] + T["rows"]])
+    return out
+
+
+def walk_tile(info, S, v):
+    cols, k, kw = info.cols, info.k, info.lo_bits
     units, stream, blk = S["units"], S["stream"], S["blk_unit"]
     vl = np.concatenate([np.asarray(v, dtype=np.int64), [0]])
     out = np.zeros(cols, dtype=np.int64)
@@ -314,9 +333,14 @@ def test_long_segments_and_big_windows_are_split_into_units():
     with HostIndex(A, 2) as h:
         S = R.rsr_host_streams(h.x)
         check_streams(h, S)
-        assert len(S["units"]) == -(-60000 // (MAX_POS * LANES)) and np.all(S["units"]["window"] == 0)
+        assert h.info.row_tiles == 2 and S["rows"] == 30000   # two row tiles of equal height
+        assert len(S["units"]) == -(-30000 // (MAX_POS * LANES)) and np.all(S["units"]["window"] == 0)
         assert 2 * h.info.stored_rows > 0.95 * h.info.index_bytes
         assert S["units"]["nheads"].sum() == 0
+        v = g.integers(-127, 128, size=60000, dtype=np.int8)
+        assert np.array_equal(walk(h, S, v), dense.matvec_i8(A, v))
+        sigma, L = R.rsr_host_export_block(h.x, 0, 0)       # the tiles together are the index of the matrix
+        assert sigma.tolist() == list(range(60000)) and L.tolist() == [0, 0, 0, 0, 60000]
     # the index of a random matrix is little more than 16 bits per row plus one flag bit
     A = g.integers(0, 2, size=(4096, 40)).astype(np.int8)
     with HostIndex(A, 10) as h:
