@@ -99,6 +99,145 @@ def cpu_baseline(A, v, dtype, budget_s):
     }, exact
 
 
+def bench_llm_block(args):
+    """--workload llm_block: one decode step of the transformer block of configuration 4 as a unit of work.
+
+    The block's seven matrices are four stages (q/k/v one index, attn_o, gate/up one index, mlp_down): a step
+    is the four products, (a) as four launches captured in one HIP graph (the stages of a real block depend on
+    each other through attention and the activation function, which are not part of this library, so they
+    stay separate kernels), (b) as four plain launches, (c) as one launch that carries all four (possible
+    only when their inputs are ready together; an upper bound).  `value` is (a)."""
+    import numpy as np
+    import torch
+
+    import paper_2411_06360_amd as R
+    import workloads
+    from oracle import dense
+
+    torch.cuda.set_device(0)
+    stages = workloads.llm_block_stages()
+    mats = [workloads.stage_matrix(members) for _, members in stages]
+    k = stages[0][1][0].k
+    batch = args.batch
+    vs = [members[0].activations(batch, "f32") for _, members in stages]
+    first = [R.rsr_preprocess(A, k) for A in mats]
+    infos = [R.rsr_info(h) for h in first]
+    table_bytes = sum(int(i.table_bytes) for i in infos)
+    ncopies = 1 if args.regime == "warm" else min(32, max(2, -(-2 * LLC_BYTES // table_bytes) + 1))
+    copies = [first] + [[R.rsr_preprocess(A, k) for A in mats] for _ in range(ncopies - 1)]
+    dv = [torch.from_numpy(v).cuda() for v in vs]
+    outs = [torch.zeros((batch, A.shape[1]), dtype=torch.float32, device="cuda") for A in mats]
+    lib = R.load()
+    cur = torch.cuda.current_stream().cuda_stream
+
+    def launches(hs, stream):
+        for h, v, o in zip(hs, dv, outs):
+            if lib.rsr_matvec(h, v.data_ptr(), o.data_ptr(), batch, stream) != 0:
+                raise RuntimeError(R.rsr_last_error())
+
+    jobs = [R.make_jobs(list(zip(hs, dv, outs))) for hs in copies]
+
+    def fused(c, stream):
+        R.rsr_matvec_multi(jobs[c], batch, stream)
+
+    launches(copies[-1], cur)
+    torch.cuda.synchronize()
+    got = [o.cpu().numpy() for o in outs]
+    side = torch.cuda.Stream()
+    graphs = []
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        launches(copies[0], side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for hs in copies:
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph, stream=side):
+            launches(hs, torch.cuda.current_stream().cuda_stream)
+        graphs.append(gph)
+
+    def timed(step_fn, steps, warm):
+        for i in range(warm):
+            step_fn(i % ncopies)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for i in range(steps):
+            step_fn((warm + i) % ncopies)
+        e1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, e0.elapsed_time(e1) * 1e3 / steps
+
+    for i in range(PRECONDITION_LAUNCHES // 4):
+        graphs[i % ncopies].replay()
+    torch.cuda.synchronize()
+    wall, graph_us = timed(lambda c: graphs[c].replay(), args.steps, args.warmup)
+    _, plain_us = timed(lambda c: launches(copies[c], cur), args.steps, args.warmup)
+    _, fused_us = timed(lambda c: fused(c, cur), args.steps, args.warmup)
+    per_stage = []
+    for si in range(len(stages)):
+        def one(c, si=si):
+            if lib.rsr_matvec(copies[c][si], dv[si].data_ptr(), outs[si].data_ptr(), batch, cur) != 0:
+                raise RuntimeError(R.rsr_last_error())
+        per_stage.append(timed(one, args.steps, args.warmup)[1])
+
+    io_bytes = sum(batch * (A.shape[0] * 4 + A.shape[1] * 4) for A in mats)
+    method_bytes = sum(int(i.parts) * int(i.nblocks) * (int(i.rows) * 2 + (1 << k) * 2) for i in infos) + io_bytes
+    stored_bytes = table_bytes + io_bytes
+    result = {
+        "metric": "RSR++ transformer-block decode step (7 ternary matrices of a ~2B-parameter 1.58-bit block as 4 products): blocks/s",
+        "value": args.steps / wall,
+        "unit": "blocks/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"llm_block: stages {[n for n, _ in stages]} with shapes {[list(A.shape) for A in mats]}, k={k}, batch {batch}, f32 activations",
+            "regime": args.regime, "index_copies_rotated": ncopies, "table_bytes": table_bytes,
+            "step": "four launches captured in one HIP graph, one replay per step",
+            "us_per_block_graph": graph_us, "us_per_block_four_launches": plain_us, "us_per_block_one_launch": fused_us,
+            "us_per_stage_alone": dict(zip([n for n, _ in stages], per_stage)),
+            "us_per_block_at_hbm_peak": stored_bytes / HBM_PEAK_GBS * 1e-3,
+            "parity_worst_error_over_bound": None,
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": method_bytes / (graph_us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": method_bytes / (graph_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "algorithmic_bytes_per_launch": method_bytes, "stored_bytes_per_launch": stored_bytes,
+            "stored_frac": stored_bytes / (graph_us * 1e-6) / 1e9 / HBM_PEAK_GBS, "launch_us": graph_us,
+            "note": "per block (four kernels); the smallest stage alone is bound by what a launch costs before its first sums",
+        },
+    }
+    if not args.no_cpu:
+        threads = dense.host_threads()
+        exact = [dense.matvec_f32(A, v, threads=threads) for A, v in zip(mats, vs)]
+        worst = 0.0
+        for g_, e_, v in zip(got, exact, vs):
+            bound = 1e-5 * np.abs(v.astype(np.float64)).sum(axis=1, keepdims=True)
+            worst = max(worst, float((np.abs(g_.astype(np.float64) - e_) / bound).max()))
+        if not worst <= 1.0:
+            print(f"parity FAILED: error is {worst:.3g} x the allowed 1e-5*sum|v|", file=sys.stderr)
+            sys.exit(1)
+        result["config"]["parity_worst_error_over_bound"] = worst
+        t0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t0 < args.cpu_seconds:
+            for A, v in zip(mats, vs):
+                dense.matvec_f32(A, v[:1], threads=threads)
+            reps += 1
+        result["cpu_baseline"] = {
+            "value": reps / (time.perf_counter() - t0), "unit": "blocks/s", "cores": threads, "kind": "oracle",
+            "sample": f"{reps} passes over the four stage matrices with one vector each, columns striped over {threads} threads",
+        }
+    torch.cuda.synchronize()
+    del graphs
+    for hs in copies:
+        for h in hs:
+            R.rsr_destroy(h)
+    print(json.dumps(result), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -115,6 +254,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.workload == "llm_block":
+        bench_llm_block(args)
+        return
     torch.cuda.set_device(0)
     w = workloads.get(args.workload)
     A = w.matrix()

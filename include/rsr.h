@@ -100,6 +100,33 @@ int rsr_matvec(rsr_handle *h, const float *v, float *out, int batch, void *strea
  */
 int rsr_matvec_i8(rsr_handle *h, const int8_t *v, int32_t *out, int batch, void *stream);
 
+/*
+ * rsr_matvec_multi / rsr_matvec_multi_i8 - several products v_j . A_j as ONE launch: the products
+ * are independent (Section 2.2 states the problem for one matrix; a transformer layer applies several
+ * fixed matrices per step, Section 5.3) and share the device, each with its own handle, activations
+ * and results.  Use it for matrices whose inputs are ready together (the q/k/v projections of one
+ * activation, gate and up), where separate launches would each pay the start of a kernel.
+ *
+ *   jobs    HOST pointer to njobs records (read during the call only); in job j, `h` is a handle,
+ *           `v` a DEVICE pointer [batch][rows_j] (float, or int8 for _i8) and `out` a DEVICE pointer
+ *           [batch][cols_j] (float, or int32), as for rsr_matvec.  Buffers of different jobs must
+ *           not overlap, except that several jobs may read the same v.
+ *   njobs   1 .. 8
+ *   batch   >= 1, the same for every job
+ *   stream  as for rsr_matvec
+ *
+ * Asynchronous, allocates nothing, results bit-identical to separate rsr_matvec calls.
+ * Errors: RSR_ERR_INVALID_ARGUMENT (null pointers, njobs or batch out of range, handles of different
+ * devices), RSR_ERR_UNSUPPORTED (a handle with more than 32768 rows: use rsr_matvec), RSR_ERR_HIP.
+ */
+typedef struct rsr_job {
+  rsr_handle *h;
+  const void *v;
+  void *out;
+} rsr_job;
+int rsr_matvec_multi(const rsr_job *jobs, int njobs, int batch, void *stream);
+int rsr_matvec_multi_i8(const rsr_job *jobs, int njobs, int batch, void *stream);
+
 /* rsr_destroy - frees the device tables and the handle.  NULL is allowed.  The caller must make
  * sure that no enqueued product still uses the handle (synchronise the stream first). */
 void rsr_destroy(rsr_handle *h);

@@ -21,5 +21,8 @@ from .binding import (  # noqa: F401
     rsr_last_error,
     rsr_matvec,
     rsr_matvec_i8,
+    rsr_matvec_multi,
+    rsr_matvec_multi_i8,
+    make_jobs,
     rsr_preprocess,
 )

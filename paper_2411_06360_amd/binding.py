@@ -85,6 +85,10 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_matvec.restype = ci
     L.rsr_matvec_i8.argtypes = [vp, vp, vp, ci, vp]
     L.rsr_matvec_i8.restype = ci
+    L.rsr_matvec_multi.argtypes = [vp, ci, ci, vp]
+    L.rsr_matvec_multi.restype = ci
+    L.rsr_matvec_multi_i8.argtypes = [vp, ci, ci, vp]
+    L.rsr_matvec_multi_i8.restype = ci
     L.rsr_destroy.argtypes = [vp]
     L.rsr_destroy.restype = None
     L.rsr_last_error.argtypes = []
@@ -151,6 +155,29 @@ def rsr_matvec(handle: int, v, out, batch: int, stream=None) -> None:
 def rsr_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
     """``v``: device int8 ``[batch][rows]``; ``out``: device int32 ``[batch][cols]``."""
     _check(load().rsr_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+class RsrJob(ctypes.Structure):
+    _fields_ = [("h", ctypes.c_void_p), ("v", ctypes.c_void_p), ("out", ctypes.c_void_p)]
+
+
+def make_jobs(jobs):
+    """A C array of rsr_job from (handle, v, out) triples; keep it alive while it is in use."""
+    arr = (RsrJob * len(jobs))()
+    for i, (h, v, out) in enumerate(jobs):
+        arr[i].h, arr[i].v, arr[i].out = int(h), _addr(v), _addr(out)
+    return arr
+
+
+def rsr_matvec_multi(jobs, batch: int, stream=None) -> None:
+    """``jobs``: (handle, v, out) triples with float activations, or an array made by make_jobs."""
+    arr = jobs if isinstance(jobs, ctypes.Array) else make_jobs(jobs)
+    _check(load().rsr_matvec_multi(ctypes.cast(arr, ctypes.c_void_p), len(arr), int(batch), _addr(stream)))
+
+
+def rsr_matvec_multi_i8(jobs, batch: int, stream=None) -> None:
+    arr = jobs if isinstance(jobs, ctypes.Array) else make_jobs(jobs)
+    _check(load().rsr_matvec_multi_i8(ctypes.cast(arr, ctypes.c_void_p), len(arr), int(batch), _addr(stream)))
 
 
 def rsr_destroy(handle: Optional[int]) -> None:

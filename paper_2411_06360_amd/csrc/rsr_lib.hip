@@ -127,6 +127,7 @@ struct KArgs {
   int row0;      // first row of this row tile
   int accumulate;  // add to `out` instead of overwriting it (second and later row tiles)
   int g1;        // workgroups per batch lane
+  int waves;     // wavefronts that take units (the LDS layout has a window for each)
   int ucap;      // unit records per round
   int nslot;     // block completion counters per round
   int nunits;    // unit descriptors in the index
@@ -344,23 +345,27 @@ constexpr int NG = rsr::kMaxGranules;
 #define RSR_HEAD_GRANULES 1
 #endif
 
+// The work of one workgroup: `wg` is its number among the workgroups of this product (a launch may
+// carry several products, see rsr_multi_kernel).  The workgroup may have more wavefronts than the
+// product's LDS layout has windows for (p.waves): the others help to stage the activation vector
+// and take no units.
 template <typename VT>
-__global__ void __launch_bounds__(1024)
-rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
-                  const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
-                  typename Acc<VT>::type* __restrict__ out, const KArgs p) {
+__device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
+                                         const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
+                                         typename Acc<VT>::type* __restrict__ out, const KArgs& p, const int wg) {
   using AT = typename Acc<VT>::type;
   extern __shared__ __align__(16) unsigned char lds[];
   VT* vl = reinterpret_cast<VT*>(lds);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nwaves = (int)(blockDim.x >> 6);
+  const int nwaves = p.waves;
+  const bool worker = wave < nwaves;
 
   // workgroup -> (batch lane b, block range g): the `batch` siblings of a block range sit 8
   // workgroup ids apart so that round-robin dispatch puts them on the same XCD (shared L2).
   const int per = 8 * p.batch;
-  const int grp = blockIdx.x / per, rem = blockIdx.x % per;
+  const int grp = wg / per, rem = wg % per;
   const int b = rem >> 3;
   const int g = grp * 8 + (rem & 7);
   if (g >= p.g1) return;
@@ -368,7 +373,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   const int blk_end = (int)((int64_t)(g + 1) * p.nblocks / p.g1);
   if (blk_begin >= blk_end) return;
 
-  const uint32_t winbase = p.off_win + (uint32_t)wave * (rsr::kWindow * 4);
+  const uint32_t winbase = p.off_win + (uint32_t)(worker ? wave : 0) * (rsr::kWindow * 4);
   AT* win = reinterpret_cast<AT*>(lds + winbase);
   AT* rec = reinterpret_cast<AT*>(lds + p.off_rec);
   unsigned* done = reinterpret_cast<unsigned*>(lds + p.off_done);
@@ -472,6 +477,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     // behind it in the queue anyway.
     const uint32_t u_first = u_begin + (uint32_t)wave;
     Desc D = load_desc(unit_words, u_first < (uint32_t)p.nunits ? u_first : 0u);
+    if (!worker) D.npos = 0;  // (its loads then fall outside the buffer descriptor and read nothing)
     issue_head(D.stream_off, D.npos, eA, fA);
     if (first_round) {
       // vl[rows] = 0 serves the null row index.
@@ -504,7 +510,7 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
     auto fetch_desc = [&](uint32_t ixq) {  // past the end it reads unit 0 (unused)
       return load_desc(unit_words, ixq < n_tot ? u_begin + ixq : 0u);
     };
-    uint32_t ix = (uint32_t)wave;
+    uint32_t ix = worker ? (uint32_t)wave : n_tot;
 
     // One unit from buffer (e, et, f); the next unit's stream goes into (en, etn, fn) meanwhile.
     auto unit = [&](uint32_t (&e)[NG][4], uint32_t (&et)[4], uint32_t (&f)[2], uint32_t (&en)[NG][4], uint32_t (&etn)[4],
@@ -679,14 +685,63 @@ rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __re
   }
 }
 
+template <typename VT>
+__global__ void __launch_bounds__(1024)
+rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
+                  const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
+                  typename Acc<VT>::type* __restrict__ out, const KArgs p) {
+  rsr_body<VT>(stream, unit_words, blk_unit, vin, out, p, (int)blockIdx.x);
+}
+
+// Several products in one launch (rsr_matvec_multi): every product owns a range of workgroups and
+// brings its own tables, activations, results and LDS layout.
+constexpr int kMaxJobs = 8;
+struct KJob {
+  const unsigned char* stream;
+  const uint32_t* unit_words;
+  const uint32_t* blk_unit;
+  const void* vin;
+  void* out;
+  int wg_begin;  // first workgroup of this product
+  int pad;
+  KArgs p;
+};
+struct MultiArgs {
+  int njobs;
+  int pad;
+  KJob job[kMaxJobs];
+};
+
+template <typename VT>
+__global__ void __launch_bounds__(1024) rsr_multi_kernel(const MultiArgs m) {
+  int j = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxJobs; ++i)
+    if (i < m.njobs && (int)blockIdx.x >= m.job[i].wg_begin) j = i;
+  // (selected with a wavefront-uniform index: the arguments stay in scalar registers)
+  const KJob& J = m.job[j];
+  rsr_body<VT>(J.stream, J.unit_words, J.blk_unit, static_cast<const VT*>(J.vin),
+               static_cast<typename Acc<VT>::type*>(J.out), J.p, (int)blockIdx.x - J.wg_begin);
+}
+
 // ---------------------------------------------------------------------------------------------
 // host code
 // ---------------------------------------------------------------------------------------------
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-template <typename VT>
-int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v, void* out, int batch, void* stream) {
+struct LaunchPlan {
   KArgs p;
+  int64_t grid = 0;
+  int waves = 0;
+  size_t lds = 0;
+};
+
+// Launch shape of one row tile for `batch` vectors on `num_cu` compute units.
+// `max_wg_per_cu`: how many workgroups of this product may share a compute unit (a launch that carries
+// several products gives every workgroup the largest LDS size any of them needs, so it plans with 1).
+template <typename VT>
+int plan_tile(const rsr_handle* h, const DeviceTile& T, bool accumulate, int batch, int num_cu, int max_wg_per_cu, LaunchPlan* plan) {
+  KArgs& p = plan->p;
   std::memset(&p, 0, sizeof(p));
   p.rows = (int)T.rows; p.cols = (int)h->cols; p.k = h->k; p.kw = h->kw; p.parts = h->parts;
   p.nblocks = (int)h->nblocks; p.last_width = h->last_width; p.batch = batch;
@@ -718,8 +773,8 @@ int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v
   const int waves_fit = waves;
   const size_t ucap_fit = ucap;
   int64_t g1 = 1;
-  for (int wg = 4; wg >= 1; --wg) {
-    g1 = ((int64_t)h->num_cu * wg + batch - 1) / batch;
+  for (int wg = max_wg_per_cu; wg >= 1; --wg) {
+    g1 = ((int64_t)num_cu * wg + batch - 1) / batch;
     g1 = (g1 + 7) / 8 * 8;
     if (g1 > h->nblocks) g1 = h->nblocks;
     if (g1 < 1) g1 = 1;
@@ -738,7 +793,10 @@ int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v
   const int64_t grid = (g1 + 7) / 8 * 8 * (int64_t)batch;
   if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
 
-  const size_t lds = total(waves, ucap);
+  plan->lds = total(waves, ucap);
+  plan->grid = grid;
+  plan->waves = waves;
+  p.waves = waves;
   p.ucap = (int)ucap; p.nslot = nslot;
   p.off_win = (uint32_t)vbytes;
   p.off_rec = (uint32_t)(vbytes + (size_t)waves * win_bytes);
@@ -746,11 +804,83 @@ int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v
   p.off_ctr = (uint32_t)(p.off_done + (size_t)nslot * 4);
   p.off_bu = p.off_ctr + 16;
   p.nunits = (int)T.nunits;
+  return RSR_OK;
+}
 
+template <typename VT>
+int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v, void* out, int batch, void* stream) {
+  LaunchPlan plan;
+  const int rc = plan_tile<VT>(h, T, accumulate, batch, h->num_cu, 4, &plan);
+  if (rc != RSR_OK) return rc;
   auto kern = rsr_matvec_kernel<VT>;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(kern, dim3((unsigned)plan.grid), dim3((unsigned)(plan.waves * 64)), plan.lds, static_cast<hipStream_t>(stream),
                      static_cast<const unsigned char*>(T.d_stream), static_cast<const uint32_t*>(T.d_units), static_cast<const uint32_t*>(T.d_blk_unit), v,
-                     static_cast<typename Acc<VT>::type*>(out), p);
+                     static_cast<typename Acc<VT>::type*>(out), plan.p);
+  RSR_HIP_TRY(hipGetLastError());
+  return RSR_OK;
+}
+
+// Several products as one launch: the compute units are shared out in proportion to the bytes of the
+// products' tables; every product is then planned as if it had its share of the device to itself.
+template <typename VT>
+int launch_multi(const rsr_job* jobs, int njobs, int batch, void* stream) {
+  if (!jobs || njobs < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "no jobs");
+  if (njobs > kMaxJobs) return fail(RSR_ERR_INVALID_ARGUMENT, "at most " + std::to_string(kMaxJobs) + " products per launch");
+  if (batch < 1 || batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be in 1..65535");
+  double bytes_total = 0;
+  for (int j = 0; j < njobs; ++j) {
+    if (!valid(jobs[j].h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle in job " + std::to_string(j));
+    if (!jobs[j].v || !jobs[j].out) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer in job " + std::to_string(j));
+    if (jobs[j].h->tiles.size() != 1) return fail(RSR_ERR_UNSUPPORTED, "a matrix with more than 32768 rows takes a launch per row tile: use rsr_matvec");
+    if (jobs[j].h->device != jobs[0].h->device) return fail(RSR_ERR_INVALID_ARGUMENT, "the handles belong to different devices");
+    bytes_total += (double)jobs[j].h->stream_bytes + 1.0;
+  }
+  MultiArgs m;
+  std::memset(&m, 0, sizeof(m));
+  m.njobs = njobs;
+  int64_t grid = 0;
+  int waves = 1;
+  size_t lds = 0;
+  const int num_cu = jobs[0].h->num_cu;
+  // shares in multiples of 8 compute units (one per XCD), at least 8, together no more than the device has
+  // (a workgroup that has to wait for a free compute unit would start when the others are nearly done)
+  int share[kMaxJobs];
+  int given = 0;
+  for (int j = 0; j < njobs; ++j) {
+    share[j] = std::max(8, (int)((double)num_cu * ((double)jobs[j].h->stream_bytes + 1.0) / bytes_total) / 8 * 8);
+    given += share[j];
+  }
+  while (given > num_cu) {
+    int big = 0;
+    for (int j = 1; j < njobs; ++j) if (share[j] > share[big]) big = j;
+    if (share[big] <= 8) break;
+    share[big] -= 8; given -= 8;
+  }
+  while (given + 8 <= num_cu) {  // what is left over goes to the products with the most bytes per compute unit
+    int best = 0;
+    for (int j = 1; j < njobs; ++j)
+      if ((double)jobs[j].h->stream_bytes / share[j] > (double)jobs[best].h->stream_bytes / share[best]) best = j;
+    share[best] += 8; given += 8;
+  }
+  for (int j = 0; j < njobs; ++j) {
+    rsr_handle* h = jobs[j].h;
+    LaunchPlan plan;
+    const int rc = plan_tile<VT>(h, h->tiles[0], false, batch, std::min(share[j], num_cu), 1, &plan);
+    if (rc != RSR_OK) return rc;
+    KJob& J = m.job[j];
+    J.stream = static_cast<const unsigned char*>(h->tiles[0].d_stream);
+    J.unit_words = static_cast<const uint32_t*>(h->tiles[0].d_units);
+    J.blk_unit = static_cast<const uint32_t*>(h->tiles[0].d_blk_unit);
+    J.vin = jobs[j].v; J.out = jobs[j].out;
+    J.wg_begin = (int)grid;
+    J.p = plan.p;
+    grid += plan.grid;  // (a multiple of 8: every product starts on the first XCD of the round-robin)
+    waves = std::max(waves, plan.waves);
+    lds = std::max(lds, plan.lds);
+    if (grid > 0x7fffffff) return fail(RSR_ERR_INVALID_ARGUMENT, "batch too large");
+  }
+  auto kern = rsr_multi_kernel<VT>;
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)(waves * 64)), lds, static_cast<hipStream_t>(stream), m);
   RSR_HIP_TRY(hipGetLastError());
   return RSR_OK;
 }
@@ -827,7 +957,9 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   h->flag_bytes = info.segment_bytes; h->stream_bytes = info.index_bytes + info.segment_bytes; h->schedule_bytes = info.schedule_bytes;
   // both kernels may use the whole LDS of a compute unit as dynamic shared memory
   for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float>),
-                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>)}) {
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>),
+                           reinterpret_cast<const void*>(rsr_multi_kernel<float>),
+                           reinterpret_cast<const void*>(rsr_multi_kernel<int8_t>)}) {
     e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_max);
     if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e)); return nullptr; }
   }
@@ -849,6 +981,14 @@ int rsr_matvec(rsr_handle* h, const float* v, float* out, int batch, void* strea
 
 int rsr_matvec_i8(rsr_handle* h, const int8_t* v, int32_t* out, int batch, void* stream) {
   return launch<int8_t>(h, v, out, batch, stream);
+}
+
+int rsr_matvec_multi(const rsr_job* jobs, int njobs, int batch, void* stream) {
+  return launch_multi<float>(jobs, njobs, batch, stream);
+}
+
+int rsr_matvec_multi_i8(const rsr_job* jobs, int njobs, int batch, void* stream) {
+  return launch_multi<int8_t>(jobs, njobs, batch, stream);
 }
 
 void rsr_destroy(rsr_handle* h) {

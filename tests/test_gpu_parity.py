@@ -262,6 +262,103 @@ def test_product_captured_in_a_graph_gives_the_eager_result_on_every_replay():
             assert_f32_close(out.cpu().numpy(), dense.matvec_f32(A, v), v)
 
 
+def test_several_products_in_one_launch_equal_separate_launches():
+    """rsr_matvec_multi: products of different shapes (and kinds) share one launch; every result is
+    bit-identical to the product's own launch, and the oracle agrees."""
+    import torch
+
+    g = rng(71)
+    shapes = [(700, 333, 9, "ternary"), (2560, 500, 10, "ternary"), (64, 2000, 4, "binary"), (5000, 40, 6, "ternary")]
+    mats = [(g.integers(0, 2, size=(r, c)) if kind == "binary" else g.integers(-1, 2, size=(r, c))).astype(np.int8)
+            for r, c, k, kind in shapes]
+    hs = [R.rsr_preprocess(A, k) for A, (_, _, k, _) in zip(mats, shapes)]
+    st = torch.cuda.current_stream().cuda_stream
+    try:
+        for batch in (1, 5):
+            note(f"multi launch of {len(hs)} products, batch {batch}")
+            vfs = [g.standard_normal((batch, A.shape[0])).astype(np.float32) for A in mats]
+            dv = [torch.from_numpy(v).cuda() for v in vfs]
+            single = [torch.full((batch, A.shape[1]), float("nan"), dtype=torch.float32, device="cuda") for A in mats]
+            multi = [torch.full((batch, A.shape[1]), float("nan"), dtype=torch.float32, device="cuda") for A in mats]
+            for h, v, o in zip(hs, dv, single):
+                R.rsr_matvec(h, v, o, batch, st)
+            R.rsr_matvec_multi(list(zip(hs, dv, multi)), batch, st)
+            torch.cuda.synchronize()
+            for A, v, a, b in zip(mats, vfs, single, multi):
+                assert torch.equal(a, b)
+                assert_f32_close(b.cpu().numpy(), dense.matvec_f32(A, v), v)
+            v8s = [g.integers(-127, 128, size=(batch, A.shape[0]), dtype=np.int8) for A in mats]
+            d8 = [torch.from_numpy(v).cuda() for v in v8s]
+            o8 = [torch.full((batch, A.shape[1]), -7, dtype=torch.int32, device="cuda") for A in mats]
+            R.rsr_matvec_multi_i8(list(zip(hs, d8, o8)), batch, st)
+            torch.cuda.synchronize()
+            for A, v, o in zip(mats, v8s, o8):
+                assert np.array_equal(o.cpu().numpy().astype(np.int64), dense.matvec_i8(A, v))
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec_multi([(hs[0], dv[0], multi[0])] * 9, 1, st)   # more than 8 products
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec_multi([(hs[0], None, multi[0])], 1, st)
+    finally:
+        torch.cuda.synchronize()
+        for h in hs:
+            R.rsr_destroy(h)
+
+
+def test_llm_block_stages_one_index_per_stage_every_output_slice():
+    """Configuration 4 as the four stages of a decode step: q/k/v and gate/up are one index each (their
+    columns side by side).  Every slice of every stage's output is checked against the oracle's product
+    of the slice's own matrix, at batch 1 and 16, from separate launches and from one captured graph."""
+    import torch
+
+    stages = workloads.llm_block_stages()
+    st = torch.cuda.current_stream().cuda_stream
+    hs = []
+    try:
+        mats = [workloads.stage_matrix(members) for _, members in stages]
+        hs = [R.rsr_preprocess(A, members[0].k) for A, (_, members) in zip(mats, stages)]
+        for batch in (1, 16):
+            note(f"llm block stages, batch {batch}")
+            vs = [members[0].activations(batch, "f32") for _, members in stages]
+            dv = [torch.from_numpy(v).cuda() for v in vs]
+            outs = [torch.full((batch, A.shape[1]), float("nan"), dtype=torch.float32, device="cuda") for A in mats]
+            for h, v, o in zip(hs, dv, outs):
+                R.rsr_matvec(h, v, o, batch, st)
+            torch.cuda.synchronize()
+            for (name, members), v, o in zip(stages, vs, outs):
+                got = o.cpu().numpy()
+                c0 = 0
+                for w in members:
+                    A = w.matrix()
+                    assert_f32_close(got[:, c0 : c0 + w.cols], dense.matvec_f32(A, v, threads=dense.host_threads()), v)
+                    c0 += w.cols
+                assert c0 == got.shape[1]
+            # the four launches as one graph, replayed: same bits
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            gouts = [torch.zeros_like(o) for o in outs]
+            with torch.cuda.stream(side):
+                for h, v, o in zip(hs, dv, gouts):
+                    R.rsr_matvec(h, v, o, batch, side.cuda_stream)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for h, v, o in zip(hs, dv, gouts):
+                    R.rsr_matvec(h, v, o, batch, torch.cuda.current_stream().cuda_stream)
+            for rep in range(3):
+                for o in gouts:
+                    o.fill_(float("nan"))
+                torch.cuda.synchronize()
+                graph.replay()
+                torch.cuda.synchronize()
+                for a, b in zip(outs, gouts):
+                    assert torch.equal(a, b), f"graph replay {rep} differs"
+    finally:
+        torch.cuda.synchronize()
+        for h in hs:
+            R.rsr_destroy(h)
+
+
 def test_unaligned_activation_pointer_and_odd_row_count():
     import torch
 

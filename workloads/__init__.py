@@ -17,6 +17,8 @@ from .configs import (  # noqa: F401
     binary_matrix,
     correlated_ternary_matrix,
     get,
+    llm_block_stages,
+    stage_matrix,
     make_activations,
     seed_for,
     ternary_matrix,

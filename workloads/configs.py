@@ -153,6 +153,23 @@ CONFIGS: Dict[int, List[Workload]] = {
 }
 
 
+def llm_block_stages() -> List[Tuple[str, List[Workload]]]:
+    """Config 4 as the four matrix stages of one decode step of the block: the projections that read the
+    same activation are one matrix (their columns side by side), so a stage is one index and one product.
+    Returns (stage name, the config-4 matrices it concatenates) in the order the block applies them."""
+    by = {w.name.split(".")[1]: w for w in CONFIGS[4]}
+    return [
+        ("qkv", [by["attn_q"], by["attn_k"], by["attn_v"]]),      # 2560 x 7680
+        ("attn_o", [by["attn_o"]]),                               # 2560 x 2560
+        ("gate_up", [by["mlp_gate"], by["mlp_up"]]),              # 2560 x 13824
+        ("mlp_down", [by["mlp_down"]]),                           # 6912 x 2560
+    ]
+
+
+def stage_matrix(members: List[Workload]) -> np.ndarray:
+    return np.ascontiguousarray(np.concatenate([w.matrix() for w in members], axis=1))
+
+
 def get(name: str) -> Workload:
     for ws in CONFIGS.values():
         for w in ws:
