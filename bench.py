@@ -56,6 +56,8 @@ def parse_args():
     ap.add_argument("--regime", choices=("cold", "warm"), default="cold")
     ap.add_argument("--workload", default="binary_16k")
     ap.add_argument("--dtype", choices=("f32", "i8"), default="f32")
+    ap.add_argument("--step2", choices=("fold", "plain"), default="fold",
+                    help="step 2 as the RSR++ fold (Algorithm 3) or as the plain product of Algorithm 2 (for comparison)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg and with it the parity check (profiling runs)")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the CPU leg's product")
@@ -273,6 +275,9 @@ def main():
     else:
         ncopies = 1
     handles = [first] + [R.rsr_preprocess(A, w.k) for _ in range(ncopies - 1)]
+    if args.step2 == "plain":
+        for h in handles:
+            R.rsr_set_step2(h, R.RSR_STEP2_PLAIN)
 
     dv = torch.from_numpy(v).cuda()
     out_dtype = torch.float32 if args.dtype == "f32" else torch.int32
@@ -368,6 +373,7 @@ def main():
         "config": {
             "workload": f"{w.name}: {w.kind} {rows}x{cols}, k={w.k}, batch {args.batch}, {args.dtype} activations",
             "regime": args.regime,
+            "step2": args.step2,
             "index_copies_rotated": ncopies,
             "untimed_conditioning_launches": PRECONDITION_LAUNCHES,
             "working_set_bytes": ncopies * table_bytes,

@@ -127,6 +127,36 @@ typedef struct rsr_job {
 int rsr_matvec_multi(const rsr_job *jobs, int njobs, int batch, void *stream);
 int rsr_matvec_multi_i8(const rsr_job *jobs, int njobs, int batch, void *stream);
 
+/*
+ * rsr_set_step2 - which form of step 2 (the product of the segmented sums u with Bin_[k]) later
+ * rsr_matvec / rsr_matvec_i8 calls on this handle use:
+ *   RSR_STEP2_FOLD   the RSR++ halving fold of Section 4.3 / Algorithm 3, O(2^k) (the default);
+ *   RSR_STEP2_PLAIN  step 2 of Algorithm 2 as printed: the plain product u . Bin_[k], O(k 2^k).
+ * Both give the same product (bit-identical for int8; the float sums are taken in another order).
+ * The plain form exists to measure what the fold is worth (Appendix F.2); rsr_matvec_multi always folds.
+ */
+enum { RSR_STEP2_FOLD = 0, RSR_STEP2_PLAIN = 1 };
+int rsr_set_step2(rsr_handle *h, int step2);
+
+/*
+ * rsr_model_k - the block width that minimises the paper's cost of RSR++, (rows + 2^k) / k per
+ * column (Section 4.3, the optimal-k equation for RSR++), over k_min .. k_max.  A formula, no device
+ * work; returns k, or a negative rsr_status.
+ *
+ * rsr_autotune_k - the empirical choice (the paper picks k by measurement too, Appendix F.1): for every
+ * k in k_min .. k_max the matrix is preprocessed on the current device and `reps` products of `batch`
+ * float vectors are timed (after warm-up calls, with events on the default stream).
+ *   A, rows, cols   as for rsr_preprocess (HOST)
+ *   cold            nonzero: rotate over enough copies of the index (at most 16) that a call does not
+ *                   find its tables in the last-level cache; zero: one copy, called back to back
+ *   best_k          HOST out: the k with the shortest product
+ *   us_per_k        HOST out or NULL: k_max - k_min + 1 durations in microseconds per product
+ * Synchronous; allocates and frees device memory of its own.  Returns RSR_OK or a negative status.
+ */
+int rsr_model_k(int64_t rows, int k_min, int k_max);
+int rsr_autotune_k(const int8_t *A, int64_t rows, int64_t cols, int batch, int k_min, int k_max,
+                   int reps, int cold, int *best_k, double *us_per_k);
+
 /* rsr_destroy - frees the device tables and the handle.  NULL is allowed.  The caller must make
  * sure that no enqueued product still uses the handle (synchronise the stream first). */
 void rsr_destroy(rsr_handle *h);

@@ -24,5 +24,10 @@ from .binding import (  # noqa: F401
     rsr_matvec_multi,
     rsr_matvec_multi_i8,
     make_jobs,
+    rsr_model_k,
+    rsr_autotune_k,
+    rsr_set_step2,
+    RSR_STEP2_FOLD,
+    RSR_STEP2_PLAIN,
     rsr_preprocess,
 )

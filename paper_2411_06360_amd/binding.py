@@ -89,6 +89,12 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_matvec_multi.restype = ci
     L.rsr_matvec_multi_i8.argtypes = [vp, ci, ci, vp]
     L.rsr_matvec_multi_i8.restype = ci
+    L.rsr_set_step2.argtypes = [vp, ci]
+    L.rsr_set_step2.restype = ci
+    L.rsr_model_k.argtypes = [i64, ci, ci]
+    L.rsr_model_k.restype = ci
+    L.rsr_autotune_k.argtypes = [vp, i64, i64, ci, ci, ci, ci, ci, ctypes.POINTER(ci), vp]
+    L.rsr_autotune_k.restype = ci
     L.rsr_destroy.argtypes = [vp]
     L.rsr_destroy.restype = None
     L.rsr_last_error.argtypes = []
@@ -155,6 +161,31 @@ def rsr_matvec(handle: int, v, out, batch: int, stream=None) -> None:
 def rsr_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
     """``v``: device int8 ``[batch][rows]``; ``out``: device int32 ``[batch][cols]``."""
     _check(load().rsr_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+RSR_STEP2_FOLD, RSR_STEP2_PLAIN = 0, 1
+
+
+def rsr_set_step2(handle: int, step2: int) -> None:
+    """Step 2 as the RSR++ fold (RSR_STEP2_FOLD, default) or as the plain product (RSR_STEP2_PLAIN)."""
+    _check(load().rsr_set_step2(handle, int(step2)))
+
+
+def rsr_model_k(rows: int, k_min: int, k_max: int) -> int:
+    k = load().rsr_model_k(int(rows), int(k_min), int(k_max))
+    if k < 0:
+        raise RsrError(k, rsr_last_error())
+    return k
+
+
+def rsr_autotune_k(A, batch: int, k_min: int, k_max: int, reps: int = 50, cold: bool = True):
+    """Returns (best k, {k: microseconds per product})."""
+    A = _host_matrix(A)
+    best = ctypes.c_int(0)
+    us = np.zeros(k_max - k_min + 1, dtype=np.float64)
+    _check(load().rsr_autotune_k(A.ctypes.data, A.shape[0], A.shape[1], int(batch), int(k_min), int(k_max), int(reps),
+                                 1 if cold else 0, ctypes.byref(best), us.ctypes.data))
+    return int(best.value), {k_min + i: float(x) for i, x in enumerate(us)}
 
 
 class RsrJob(ctypes.Structure):

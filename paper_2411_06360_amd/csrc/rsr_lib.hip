@@ -84,6 +84,7 @@ struct rsr_handle {
   int64_t flag_bytes = 0, stream_bytes = 0, schedule_bytes = 0;
   std::vector<DeviceTile> tiles;
   int waves = 16;  // wavefronts per workgroup at most
+  bool step2_plain = false;  // rsr_set_step2
   // host copy of the device tables, fetched on the first rsr_export_block
   std::unique_ptr<rsr::Index> downloaded;
 };
@@ -156,6 +157,19 @@ __device__ __forceinline__ int wave_inclusive_scan(int x) {
   y += dpp_get<0x142, 0xa, 0xf>(y);           // row_bcast:15 into rows 1 and 3
   y += dpp_get<0x143, 0xc, 0xf>(y);           // row_bcast:31 into rows 2 and 3
   return y;
+}
+
+// Sum over the 64 lanes, returned to every lane (through a scalar register).
+template <typename AT>
+__device__ __forceinline__ AT wave_total(AT x) {
+  AT y = x + dpp_get<0x111, 0xf, 0xf>(x);
+  y += dpp_get<0x112, 0xf, 0xf>(x);
+  y += dpp_get<0x113, 0xf, 0xf>(x);
+  y += dpp_get<0x114, 0xf, 0xe>(y);
+  y += dpp_get<0x118, 0xf, 0xc>(y);
+  y += dpp_get<0x142, 0xa, 0xf>(y);
+  y += dpp_get<0x143, 0xc, 0xf>(y);
+  return __builtin_bit_cast(AT, __builtin_amdgcn_readlane(__builtin_bit_cast(int, y), 63));
 }
 
 // Sums of eight values over the 16 lanes of each DPP row, all at once: after every exchange a
@@ -349,7 +363,9 @@ constexpr int NG = rsr::kMaxGranules;
 // carry several products, see rsr_multi_kernel).  The workgroup may have more wavefronts than the
 // product's LDS layout has windows for (p.waves): the others help to stage the activation vector
 // and take no units.
-template <typename VT>
+// PLAIN selects step 2 of Algorithm 2 as printed there (the product u . Bin_[k] term by term,
+// O(k 2^k)) instead of the RSR++ fold of Algorithm 3: kept for the comparison of Appendix F.2.
+template <typename VT, bool PLAIN>
 __device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
                                          const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
                                          typename Acc<VT>::type* __restrict__ out, const KArgs& p, const int wg) {
@@ -595,6 +611,26 @@ __device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ strea
 #pragma unroll
         for (int i = 0; i < 8; ++i) u[i] = __builtin_bit_cast(AT, raw[i]);
       }
+      AT total, bit7, bit8;
+      if constexpr (PLAIN) {
+        // u . Bin_[kw] by its definition: for every column (value bit) the sum of bit * u[j] over all j.
+        AT sb[rsr::kMaxWindowBits];
+#pragma unroll
+        for (int bit = 0; bit < rsr::kMaxWindowBits; ++bit) {
+          AT acc = (AT)0;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) acc += (AT)(((8 * lane + i) >> bit) & 1) * u[i];
+          sb[bit] = wave_total<AT>(acc);
+        }
+        AT all = (AT)0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) all += u[i];
+        total = wave_total<AT>(all);  // the window's total, for the value bits above the window
+#pragma unroll
+        for (int bit = 0; bit < 7; ++bit) total = ((lane & 7) == bit) ? sb[bit] : total;  // lanes 0..6 carry the bit sums
+        bit7 = sb[7];
+        bit8 = sb[8];
+      } else {
       // vals[0..2]: the three levels inside the lane; vals[3..6]: lane bits 0..3 (value bits 3..6);
       // vals[7]: the lane's total, from which the two row-index bits (value bits 7, 8) and the
       // window total follow.
@@ -614,9 +650,10 @@ __device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ strea
       const AT s02_13 = __builtin_bit_cast(AT, h32.x) + __builtin_bit_cast(AT, h32.y);  // rows 0+2, 1+3, 0+2, 1+3
       const Swapped t16 = swap16(__builtin_bit_cast(uint32_t, s02_13));                // .x: 0+2 everywhere  .y: 1+3 everywhere
       const Swapped b16 = swap16(h32.y);                                               // .x: row 2 everywhere  .y: row 3
-      const AT total = __builtin_bit_cast(AT, t16.x) + __builtin_bit_cast(AT, t16.y);
-      const AT bit7 = __builtin_bit_cast(AT, t16.y);
-      const AT bit8 = __builtin_bit_cast(AT, b16.x) + __builtin_bit_cast(AT, b16.y);
+      total = __builtin_bit_cast(AT, t16.x) + __builtin_bit_cast(AT, t16.y);
+      bit7 = __builtin_bit_cast(AT, t16.y);
+      bit8 = __builtin_bit_cast(AT, b16.x) + __builtin_bit_cast(AT, b16.y);
+      }
       // ---- record, and completion of the block: lanes 0..7 finish the sums ----
       // One store writes the record: lanes 0..6 hold the sums of value bits 0..6, lane 7 the
       // window's total, lane 15 (second row) bit 7, lane 23 bit 8; lane 31 adds part and window.
@@ -685,12 +722,12 @@ __device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ strea
   }
 }
 
-template <typename VT>
+template <typename VT, bool PLAIN>
 __global__ void __launch_bounds__(1024)
 rsr_matvec_kernel(const unsigned char* __restrict__ stream, const uint32_t* __restrict__ unit_words,
                   const uint32_t* __restrict__ blk_unit, const VT* __restrict__ vin,
                   typename Acc<VT>::type* __restrict__ out, const KArgs p) {
-  rsr_body<VT>(stream, unit_words, blk_unit, vin, out, p, (int)blockIdx.x);
+  rsr_body<VT, PLAIN>(stream, unit_words, blk_unit, vin, out, p, (int)blockIdx.x);
 }
 
 // Several products in one launch (rsr_matvec_multi): every product owns a range of workgroups and
@@ -720,7 +757,7 @@ __global__ void __launch_bounds__(1024) rsr_multi_kernel(const MultiArgs m) {
     if (i < m.njobs && (int)blockIdx.x >= m.job[i].wg_begin) j = i;
   // (selected with a wavefront-uniform index: the arguments stay in scalar registers)
   const KJob& J = m.job[j];
-  rsr_body<VT>(J.stream, J.unit_words, J.blk_unit, static_cast<const VT*>(J.vin),
+  rsr_body<VT, false>(J.stream, J.unit_words, J.blk_unit, static_cast<const VT*>(J.vin),
                static_cast<typename Acc<VT>::type*>(J.out), J.p, (int)blockIdx.x - J.wg_begin);
 }
 
@@ -812,7 +849,7 @@ int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v
   LaunchPlan plan;
   const int rc = plan_tile<VT>(h, T, accumulate, batch, h->num_cu, 4, &plan);
   if (rc != RSR_OK) return rc;
-  auto kern = rsr_matvec_kernel<VT>;
+  auto kern = h->step2_plain ? rsr_matvec_kernel<VT, true> : rsr_matvec_kernel<VT, false>;
   hipLaunchKernelGGL(kern, dim3((unsigned)plan.grid), dim3((unsigned)(plan.waves * 64)), plan.lds, static_cast<hipStream_t>(stream),
                      static_cast<const unsigned char*>(T.d_stream), static_cast<const uint32_t*>(T.d_units), static_cast<const uint32_t*>(T.d_blk_unit), v,
                      static_cast<typename Acc<VT>::type*>(out), plan.p);
@@ -956,8 +993,10 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
   h->stored_rows = info.stored_rows; h->segments = info.segments; h->nunits = info.work_units;
   h->flag_bytes = info.segment_bytes; h->stream_bytes = info.index_bytes + info.segment_bytes; h->schedule_bytes = info.schedule_bytes;
   // both kernels may use the whole LDS of a compute unit as dynamic shared memory
-  for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float>),
-                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t>),
+  for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float, false>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t, false>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<float, true>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t, true>),
                            reinterpret_cast<const void*>(rsr_multi_kernel<float>),
                            reinterpret_cast<const void*>(rsr_multi_kernel<int8_t>)}) {
     e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_max);
@@ -989,6 +1028,85 @@ int rsr_matvec_multi(const rsr_job* jobs, int njobs, int batch, void* stream) {
 
 int rsr_matvec_multi_i8(const rsr_job* jobs, int njobs, int batch, void* stream) {
   return launch_multi<int8_t>(jobs, njobs, batch, stream);
+}
+
+int rsr_set_step2(rsr_handle* h, int step2) {
+  if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
+  if (step2 != RSR_STEP2_FOLD && step2 != RSR_STEP2_PLAIN) return fail(RSR_ERR_INVALID_ARGUMENT, "unknown step 2 variant");
+  h->step2_plain = (step2 == RSR_STEP2_PLAIN);
+  return RSR_OK;
+}
+
+int rsr_model_k(int64_t rows, int k_min, int k_max) {
+  if (rows < 1 || k_min < 1 || k_max > rsr::kMaxK || k_min > k_max) return fail(RSR_ERR_INVALID_ARGUMENT, "rsr_model_k: bad range");
+  int best = k_min;
+  double best_cost = 0;
+  for (int k = k_min; k <= k_max; ++k) {
+    const double cost = ((double)rows + (double)(1u << k)) / (double)k;  // per column: (n + 2^k) / k
+    if (k == k_min || cost < best_cost) { best = k; best_cost = cost; }
+  }
+  return best;
+}
+
+int rsr_autotune_k(const int8_t* A, int64_t rows, int64_t cols, int batch, int k_min, int k_max, int reps, int cold,
+                   int* best_k, double* us_per_k) {
+  g_error.clear();
+  if (!A || !best_k) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer");
+  if (k_min < 1 || k_max > rsr::kMaxK || k_min > k_max) return fail(RSR_ERR_INVALID_ARGUMENT, "k range must lie in 1..16");
+  if (batch < 1 || batch > 65535 || reps < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch and reps must be >= 1");
+  float* v = nullptr;
+  float* out = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  std::vector<rsr_handle*> hs;
+  auto cleanup = [&]() {
+    (void)hipDeviceSynchronize();
+    for (rsr_handle* h : hs) rsr_destroy(h);
+    hs.clear();
+  };
+  auto release = [&]() {
+    cleanup();
+    if (v) (void)hipFree(v);
+    if (out) (void)hipFree(out);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+  auto bail = [&](int code, const std::string& msg) { release(); return fail(code, msg); };
+  if (hipMalloc(&v, (size_t)batch * rows * sizeof(float)) != hipSuccess || hipMalloc(&out, (size_t)batch * cols * sizeof(float)) != hipSuccess)
+    return bail(RSR_ERR_HIP, "rsr_autotune_k: device allocation failed");
+  if (hipMemset(v, 0, (size_t)batch * rows * sizeof(float)) != hipSuccess) return bail(RSR_ERR_HIP, "rsr_autotune_k: hipMemset failed");
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return bail(RSR_ERR_HIP, "rsr_autotune_k: hipEventCreate failed");
+  double best_us = 0;
+  for (int k = k_min; k <= k_max; ++k) {
+    rsr_handle* h = rsr_preprocess(A, rows, cols, k);
+    if (!h) { const std::string msg = g_error; return bail(RSR_ERR_INVALID_ARGUMENT, msg); }
+    hs.push_back(h);
+    if (cold) {  // enough copies that the tables of consecutive calls do not come from the last-level cache
+      rsr_info_t info;
+      rsr_info(h, &info);
+      const int64_t want = ((int64_t)512 << 20) / std::max<int64_t>(1, info.table_bytes) + 1;
+      const int copies = (int)std::min<int64_t>(16, std::max<int64_t>(1, want));
+      for (int c = 1; c < copies; ++c) {
+        rsr_handle* hc = rsr_preprocess(A, rows, cols, k);
+        if (!hc) { const std::string msg = g_error; return bail(RSR_ERR_HIP, msg); }
+        hs.push_back(hc);
+      }
+    }
+    const int n = (int)hs.size();
+    int rc = RSR_OK;
+    for (int i = 0; i < std::max(3, n) && rc == RSR_OK; ++i) rc = rsr_matvec(hs[(size_t)(i % n)], v, out, batch, nullptr);
+    if (rc == RSR_OK && hipEventRecord(e0, nullptr) != hipSuccess) rc = RSR_ERR_HIP;
+    for (int i = 0; i < reps && rc == RSR_OK; ++i) rc = rsr_matvec(hs[(size_t)(i % n)], v, out, batch, nullptr);
+    if (rc == RSR_OK && (hipEventRecord(e1, nullptr) != hipSuccess || hipEventSynchronize(e1) != hipSuccess)) rc = RSR_ERR_HIP;
+    float ms = 0;
+    if (rc == RSR_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) rc = RSR_ERR_HIP;
+    if (rc != RSR_OK) { const std::string msg = g_error.empty() ? "rsr_autotune_k: timing failed" : g_error; return bail(rc, msg); }
+    const double us = (double)ms * 1e3 / reps;
+    if (us_per_k) us_per_k[k - k_min] = us;
+    if (k == k_min || us < best_us) { best_us = us; *best_k = k; }
+    cleanup();
+  }
+  release();
+  return RSR_OK;
 }
 
 void rsr_destroy(rsr_handle* h) {

@@ -359,6 +359,44 @@ def test_llm_block_stages_one_index_per_stage_every_output_slice():
             R.rsr_destroy(h)
 
 
+def test_plain_step2_gives_the_same_product_as_the_fold():
+    """Step 2 of Algorithm 2 as printed (the plain product with Bin_[k]) against the RSR++ fold of Algorithm 3:
+    the same product from the same index; int8 bit for bit."""
+    g = rng(73)
+    for rows, cols, k, kind in [(3000, 200, 11, "ternary"), (700, 26, 13, "ternary"), (300, 64, 8, "binary"), (50, 37, 3, "ternary")]:
+        A = (g.integers(0, 2, size=(rows, cols)) if kind == "binary" else g.integers(-1, 2, size=(rows, cols))).astype(np.int8)
+        note(f"plain step 2: {rows}x{cols} k={k}")
+        with DeviceIndex(A, k) as d:
+            v8 = g.integers(-127, 128, size=(2, rows), dtype=np.int8)
+            vf = g.standard_normal((2, rows)).astype(np.float32)
+            fold8, foldf = d.matvec(v8), d.matvec(vf)
+            R.rsr_set_step2(d.handle, R.RSR_STEP2_PLAIN)
+            plain8, plainf = d.matvec(v8), d.matvec(vf)
+            R.rsr_set_step2(d.handle, R.RSR_STEP2_FOLD)
+            assert np.array_equal(plain8, fold8) and np.array_equal(plain8.astype(np.int64), dense.matvec_i8(A, v8))
+            assert_f32_close(plainf, dense.matvec_f32(A, vf), vf)
+            assert np.array_equal(d.matvec(vf), foldf)
+            with pytest.raises(R.RsrError):
+                R.rsr_set_step2(d.handle, 7)
+
+
+def test_autotuned_k_is_never_worse_than_a_fixed_k():
+    """The empirical block width (Section 4.3's optimal k, chosen by measurement as in Appendix F.1): the k it
+    returns is the fastest of the range it timed, so in particular not slower than the configuration's fixed k."""
+    w = workloads.get("ternary_4k")
+    A = w.matrix()[:, :1500].copy()
+    note("autotune k on ternary 4096x1500")
+    best, us = R.rsr_autotune_k(A, 1, 7, 13, reps=60, cold=False)
+    note(f"  us per product by k: { {k: round(x, 2) for k, x in us.items()} } -> best k = {best}")
+    assert 7 <= best <= 13 and us[best] == min(us.values())
+    assert us[best] <= us[w.k]
+    assert all(x > 0 for x in us.values())
+    assert R.rsr_model_k(4096, 1, 16) == 9 and R.rsr_model_k(16384, 1, 16) == 11  # argmin of (n + 2^k) / k
+    with DeviceIndex(A, best) as d:  # and the product at that k is the product
+        vf = w.activations(1, "f32")
+        assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+
+
 def test_unaligned_activation_pointer_and_odd_row_count():
     import torch
 
