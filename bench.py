@@ -58,6 +58,8 @@ def parse_args():
     ap.add_argument("--dtype", choices=("f32", "i8"), default="f32")
     ap.add_argument("--step2", choices=("fold", "plain"), default="fold",
                     help="step 2 as the RSR++ fold (Algorithm 3) or as the plain product of Algorithm 2 (for comparison)")
+    ap.add_argument("--comparator", choices=("none", "dense"), default="none",
+                    help="dense: time the bit-packed comparator (include/rsr_dense.h) instead of the RSR++ path, same protocol")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg and with it the parity check (profiling runs)")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the CPU leg's product")
@@ -266,16 +268,21 @@ def main():
     rows, cols = A.shape
 
     # ---- index copies -------------------------------------------------------------------------
+    dense_mode = args.comparator == "dense"
     first = R.rsr_preprocess(A, w.k)
     info = R.rsr_info(first)
     table_bytes = int(info.table_bytes)
+    if dense_mode:  # the comparator: same inputs, same rotation and timing, other tables and kernels
+        R.rsr_destroy(first)
+        first = R.rsr_dense_preprocess(A)
+        table_bytes = R.rsr_dense_table_bytes(first)
     if args.regime == "cold":
         ncopies = max(2, -(-2 * LLC_BYTES // table_bytes) + 1)
         ncopies = min(ncopies, 64)
     else:
         ncopies = 1
-    handles = [first] + [R.rsr_preprocess(A, w.k) for _ in range(ncopies - 1)]
-    if args.step2 == "plain":
+    handles = [first] + [(R.rsr_dense_preprocess(A) if dense_mode else R.rsr_preprocess(A, w.k)) for _ in range(ncopies - 1)]
+    if args.step2 == "plain" and not dense_mode:
         for h in handles:
             R.rsr_set_step2(h, R.RSR_STEP2_PLAIN)
 
@@ -284,6 +291,8 @@ def main():
     dout = torch.zeros((args.batch, cols), dtype=out_dtype, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     call = R.rsr_matvec if args.dtype == "f32" else R.rsr_matvec_i8
+    if dense_mode:
+        call = R.rsr_dense_matvec if args.dtype == "f32" else R.rsr_dense_matvec_i8
 
     # ---- one product at full size, in the launch configuration that is timed: kept for the check
     #      against the oracle's product, which the CPU leg below computes ---------------------------
@@ -294,6 +303,8 @@ def main():
     # ---- timed region -------------------------------------------------------------------------------
     lib = R.load()
     fn = lib.rsr_matvec if args.dtype == "f32" else lib.rsr_matvec_i8
+    if dense_mode:
+        fn = lib.rsr_dense_matvec if args.dtype == "f32" else lib.rsr_dense_matvec_i8
     pv, po = dv.data_ptr(), dout.data_ptr()
 
     def run(n, offset=0):
@@ -417,7 +428,10 @@ def main():
             result["config"]["parity_worst_error_over_bound"] = parity
     torch.cuda.synchronize()
     for h in handles:
-        R.rsr_destroy(h)
+        (R.rsr_dense_destroy if dense_mode else R.rsr_destroy)(h)
+    if dense_mode:
+        result["metric"] = f"bit-packed comparator v.A matvecs/s ({args.workload})"
+        result["config"]["comparator"] = "dense bit-packed matrix with a table of sums per four rows (two kernels per product)"
     print(json.dumps(result), flush=True)
 
 

@@ -24,6 +24,11 @@ from .binding import (  # noqa: F401
     rsr_matvec_multi,
     rsr_matvec_multi_i8,
     make_jobs,
+    rsr_dense_preprocess,
+    rsr_dense_matvec,
+    rsr_dense_matvec_i8,
+    rsr_dense_table_bytes,
+    rsr_dense_destroy,
     rsr_model_k,
     rsr_autotune_k,
     rsr_set_step2,

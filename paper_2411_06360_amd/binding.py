@@ -114,6 +114,16 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_host_streams.argtypes = ([vp, ci] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 2 + [ctypes.POINTER(vp)]
                                    + [ctypes.POINTER(i64)] * 2)
     L.rsr_host_streams.restype = ci
+    L.rsr_dense_preprocess.argtypes = [vp, i64, i64]
+    L.rsr_dense_preprocess.restype = vp
+    L.rsr_dense_matvec.argtypes = [vp, vp, vp, ci, vp]
+    L.rsr_dense_matvec.restype = ci
+    L.rsr_dense_matvec_i8.argtypes = [vp, vp, vp, ci, vp]
+    L.rsr_dense_matvec_i8.restype = ci
+    L.rsr_dense_table_bytes.argtypes = [vp]
+    L.rsr_dense_table_bytes.restype = i64
+    L.rsr_dense_destroy.argtypes = [vp]
+    L.rsr_dense_destroy.restype = None
     _lib = L
     return L
 
@@ -186,6 +196,32 @@ def rsr_autotune_k(A, batch: int, k_min: int, k_max: int, reps: int = 50, cold: 
     _check(load().rsr_autotune_k(A.ctypes.data, A.shape[0], A.shape[1], int(batch), int(k_min), int(k_max), int(reps),
                                  1 if cold else 0, ctypes.byref(best), us.ctypes.data))
     return int(best.value), {k_min + i: float(x) for i, x in enumerate(us)}
+
+
+# ---- the bit-packed comparator (include/rsr_dense.h) ----
+def rsr_dense_preprocess(A) -> int:
+    A = _host_matrix(A)
+    h = load().rsr_dense_preprocess(A.ctypes.data, A.shape[0], A.shape[1])
+    if not h:
+        raise RsrError(-1, rsr_last_error())
+    return int(h)
+
+
+def rsr_dense_matvec(handle: int, v, out, batch: int, stream=None) -> None:
+    _check(load().rsr_dense_matvec(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_dense_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
+    _check(load().rsr_dense_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_dense_table_bytes(handle: int) -> int:
+    return int(load().rsr_dense_table_bytes(handle))
+
+
+def rsr_dense_destroy(handle: Optional[int]) -> None:
+    if handle:
+        load().rsr_dense_destroy(handle)
 
 
 class RsrJob(ctypes.Structure):

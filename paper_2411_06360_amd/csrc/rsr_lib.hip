@@ -49,6 +49,15 @@ int fail(int code, const std::string& msg) {
   return code;
 }
 
+}  // namespace
+
+namespace rsr_internal {
+// shared with the other translation units of the library (rsr_dense.hip)
+int set_error(int code, const std::string& msg) { return fail(code, msg); }
+}  // namespace rsr_internal
+
+namespace {
+
 #define RSR_HIP_TRY(expr)                                                                   \
   do {                                                                                      \
     hipError_t e_ = (expr);                                                                 \

@@ -397,6 +397,40 @@ def test_autotuned_k_is_never_worse_than_a_fixed_k():
         assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
 
 
+def test_dense_bit_packed_comparator_against_the_oracle():
+    """The comparator of include/rsr_dense.h (bit-packed matrix, table of sums per four rows) gives the same
+    product: int8 exact, float within the bound; ragged row and column counts, batches, both kinds."""
+    import torch
+
+    g = rng(79)
+    st = torch.cuda.current_stream().cuda_stream
+    for rows, cols, kind in [(1, 1, "binary"), (37, 300, "ternary"), (2048, 256, "binary"), (2049, 257, "ternary"),
+                             (5000, 1000, "ternary"), (16384, 700, "binary")]:
+        A = (g.integers(0, 2, size=(rows, cols)) if kind == "binary" else g.integers(-1, 2, size=(rows, cols))).astype(np.int8)
+        note(f"dense comparator {rows}x{cols} {kind}")
+        h = R.rsr_dense_preprocess(A)
+        try:
+            planes = 2 if kind == "ternary" else 1
+            assert R.rsr_dense_table_bytes(h) == planes * -(-rows // 32) * (-(-cols // 64) * 64) * 4
+            for batch in (1, 3, 16):
+                vf = g.standard_normal((batch, rows)).astype(np.float32)
+                of = torch.full((batch, cols), float("nan"), dtype=torch.float32, device="cuda")
+                R.rsr_dense_matvec(h, torch.from_numpy(vf).cuda(), of, batch, st)
+                v8 = g.integers(-128, 128, size=(batch, rows), dtype=np.int8)
+                o8 = torch.full((batch, cols), -7, dtype=torch.int32, device="cuda")
+                R.rsr_dense_matvec_i8(h, torch.from_numpy(v8).cuda(), o8, batch, st)
+                torch.cuda.synchronize()
+                assert_f32_close(of.cpu().numpy(), dense.matvec_f32(A, vf), vf)
+                assert np.array_equal(o8.cpu().numpy().astype(np.int64), dense.matvec_i8(A, v8))
+            with pytest.raises(R.RsrError):
+                R.rsr_dense_matvec(h, of, of, 17, st)
+        finally:
+            torch.cuda.synchronize()
+            R.rsr_dense_destroy(h)
+    with pytest.raises(R.RsrError):
+        R.rsr_dense_preprocess(np.full((2, 2), 3, np.int8))
+
+
 def test_unaligned_activation_pointer_and_odd_row_count():
     import torch
 

@@ -44,9 +44,23 @@ def test_library_exports_every_declared_symbol():
     names = set(re.findall(r"\b(rsr_[a-z0-9_]+)\s*\(", header))
     assert {"rsr_preprocess", "rsr_matvec", "rsr_matvec_i8", "rsr_destroy", "rsr_last_error", "rsr_info",
             "rsr_export_block", "rsr_host_pack"} <= names
+    assert {"rsr_matvec_multi", "rsr_set_step2", "rsr_model_k", "rsr_autotune_k"} <= names
     lib = R.load()
     for n in sorted(names):
         assert hasattr(lib, n), f"{n} declared in rsr.h but not exported"
+    dense_h = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "rsr_dense.h")).read(), flags=re.S)
+    dnames = set(re.findall(r"\b(rsr_dense_[a-z0-9_]+)\s*\(", dense_h))
+    assert {"rsr_dense_preprocess", "rsr_dense_matvec", "rsr_dense_matvec_i8", "rsr_dense_destroy"} <= dnames
+    for n in sorted(dnames):
+        assert hasattr(lib, n), f"{n} declared in rsr_dense.h but not exported"
+
+
+def test_block_width_by_the_papers_cost_formula():
+    # argmin over k of (n + 2^k) / k (Section 4.3), worked by hand: n = 1024: k=7 gives 164.6, k=8 160, k=9 170.7
+    assert R.rsr_model_k(1024, 1, 16) == 8
+    assert R.rsr_model_k(1024, 1, 6) == 6 and R.rsr_model_k(1024, 10, 12) == 10
+    with pytest.raises(R.RsrError):
+        R.rsr_model_k(1024, 0, 5)
 
 
 def test_info_struct_matches_the_header():
