@@ -34,6 +34,25 @@ rsr_dense *rsr_dense_preprocess(const int8_t *A, int64_t rows, int64_t cols);
 int rsr_dense_matvec(rsr_dense *h, const float *v, float *out, int batch, void *stream);
 int rsr_dense_matvec_i8(rsr_dense *h, const int8_t *v, int32_t *out, int batch, void *stream);
 
+/*
+ * rsr_dense_matvec_static - rsr_dense_matvec for callers that cannot allocate and want nothing
+ * allocated on their behalf: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The partial sums go to a buffer that is part of the library's image on the
+ * device (RSR_DENSE_STATIC_BYTES; every GPU the library runs on holds it until the process ends)
+ * instead of the buffer the handle allocated at preprocess time.  The call allocates nothing and
+ * frees nothing (no hipMalloc, hipFree or allocating library routine).
+ *   Arguments and results (bit for bit) as rsr_dense_matvec.  The device of the handle must be
+ *   current.  The buffer's address on a device is looked up once, at rsr_dense_preprocess on that
+ *   device (else at the first call there).
+ *   Fails with RSR_ERR_UNSUPPORTED when the partial sums, 4 * ceil(rows/512) * batch * cols bytes,
+ *   exceed RSR_DENSE_STATIC_BYTES, with RSR_ERR_INVALID_ARGUMENT when another device is current.
+ *   All calls on one GPU share the one buffer and it keeps what the last call left there (nothing
+ *   needs to start at zero: a call reads only what it has written itself): calls that overlap on
+ *   a GPU - other streams, other host threads, other handles - race.
+ */
+#define RSR_DENSE_STATIC_BYTES (4u << 20)
+int rsr_dense_matvec_static(rsr_dense *h, const float *v, float *out, int batch, void *stream);
+
 /* bytes of the bit planes on the device (what one product reads) */
 int64_t rsr_dense_table_bytes(const rsr_dense *h);
 

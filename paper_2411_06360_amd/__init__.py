@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     rsr_dense_preprocess,
     rsr_dense_matvec,
     rsr_dense_matvec_i8,
+    rsr_dense_matvec_static,
     rsr_dense_table_bytes,
     rsr_dense_destroy,
     rsr_model_k,

@@ -120,6 +120,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_dense_matvec.restype = ci
     L.rsr_dense_matvec_i8.argtypes = [vp, vp, vp, ci, vp]
     L.rsr_dense_matvec_i8.restype = ci
+    L.rsr_dense_matvec_static.argtypes = [vp, vp, vp, ci, vp]
+    L.rsr_dense_matvec_static.restype = ci
     L.rsr_dense_table_bytes.argtypes = [vp]
     L.rsr_dense_table_bytes.restype = i64
     L.rsr_dense_destroy.argtypes = [vp]
@@ -213,6 +215,11 @@ def rsr_dense_matvec(handle: int, v, out, batch: int, stream=None) -> None:
 
 def rsr_dense_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
     _check(load().rsr_dense_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_dense_matvec_static(handle: int, v, out, batch: int, stream=None) -> None:
+    """As rsr_dense_matvec, with the partial sums in the library's static device buffer (allocates nothing)."""
+    _check(load().rsr_dense_matvec_static(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
 
 
 def rsr_dense_table_bytes(handle: int) -> int:

@@ -13,6 +13,7 @@
 #include <cstdint>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -23,7 +24,41 @@ namespace rsr_internal {
 int set_error(int code, const std::string& msg);  // rsr_lib.hip: the thread's message for rsr_last_error()
 }
 
+// Buffer of partial sums for rsr_dense_matvec_static: part of the code object, so every GPU the library
+// runs on holds its own copy at its own address from the moment the module is loaded there.  In host
+// code the name below is only a handle for hipGetSymbolAddress; kernels get the resolved address.
+static __device__ __align__(256) unsigned char scratch[RSR_DENSE_STATIC_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices];  // per device: address of `scratch` there (nullptr = not resolved yet)
+
+// Address of the static buffer on the CURRENT device (resolved once per device, with that device
+// current); nullptr and *err set on failure.
+void* static_scratch_on_current_device(int* device, std::string* err) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    *err = e != hipSuccess ? std::string("hipGetDevice: ") + hipGetErrorString(e) : "device ordinal out of range";
+    return nullptr;
+  }
+  *device = dev;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      *err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+      return nullptr;
+    }
+    g_static_ptr[dev] = ptr;
+  }
+  return g_static_ptr[dev];
+}
 
 constexpr int kTileRows = 512;             // rows per workgroup: 128 groups of four, 16 dwords per column
 constexpr int kTileChunks = kTileRows / 32;
@@ -123,7 +158,7 @@ int dense_launch(rsr_dense* h, const VT* v, void* out, int batch, void* stream, 
   if (batch < 1 || batch > kMaxBatch) return rsr_internal::set_error(RSR_ERR_INVALID_ARGUMENT, "batch must be in 1..16");
   const size_t need = (size_t)h->ntiles * batch * h->cols * sizeof(AT);
   if (need > scratch_bytes)
-    return rsr_internal::set_error(RSR_ERR_UNSUPPORTED, "partial sums of " + std::to_string(need) + " bytes exceed the buffer of " +
+    return rsr_internal::set_error(RSR_ERR_UNSUPPORTED, "partial sums of " + std::to_string(need) + " bytes (4 * ceil(rows/512) * batch * cols) exceed the buffer of " +
                                                            std::to_string(scratch_bytes) + " bytes");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const dim3 grid((unsigned)((h->cols + kColsPerWg - 1) / kColsPerWg), (unsigned)h->ntiles);
@@ -191,6 +226,13 @@ rsr_dense* rsr_dense_preprocess(const int8_t* A, int64_t rows, int64_t cols) {
     rsr_internal::set_error(RSR_ERR_HIP, std::string("rsr_dense_preprocess: ") + hipGetErrorString(e));
     return nullptr;
   }
+  {
+    // set-up time is the right moment to find the static buffer of this device (the device is current and
+    // nothing is being captured); a failure only matters to rsr_dense_matvec_static, which reports it
+    int dev = 0;
+    std::string ignored;
+    (void)static_scratch_on_current_device(&dev, &ignored);
+  }
   h->magic = kDenseMagic;
   return h.release();
 }
@@ -198,6 +240,20 @@ rsr_dense* rsr_dense_preprocess(const int8_t* A, int64_t rows, int64_t cols) {
 int rsr_dense_matvec(rsr_dense* h, const float* v, float* out, int batch, void* stream) {
   if (!valid(h)) return rsr_internal::set_error(RSR_ERR_INVALID_ARGUMENT, "invalid dense handle");
   return dense_launch<float>(h, v, out, batch, stream, h->d_scratch, h->scratch_bytes);
+}
+
+int rsr_dense_matvec_static(rsr_dense* h, const float* v, float* out, int batch, void* stream) {
+  if (!valid(h)) return rsr_internal::set_error(RSR_ERR_INVALID_ARGUMENT, "invalid dense handle");
+  int dev = -1;
+  std::string err;
+  void* ptr = static_scratch_on_current_device(&dev, &err);
+  if (!ptr) return rsr_internal::set_error(RSR_ERR_HIP, "rsr_dense_matvec_static: " + err);
+  if (dev != h->device)
+    return rsr_internal::set_error(RSR_ERR_INVALID_ARGUMENT, "rsr_dense_matvec_static: the handle belongs to device " + std::to_string(h->device) +
+                                                                 " but device " + std::to_string(dev) + " is current");
+  // (every partial sum that the second kernel reads is written by the first kernel of the same call:
+  // what an earlier call left in the buffer is never read, nothing has to be cleared)
+  return dense_launch<float>(h, v, out, batch, stream, ptr, (size_t)RSR_DENSE_STATIC_BYTES);
 }
 
 int rsr_dense_matvec_i8(rsr_dense* h, const int8_t* v, int32_t* out, int batch, void* stream) {
