@@ -69,6 +69,23 @@ typedef struct rsr_handle rsr_handle; /* opaque; owns the device-resident index 
 rsr_handle *rsr_preprocess(const int8_t *A, int64_t rows, int64_t cols, int k);
 
 /*
+ * rsr_preprocess_device - Algorithm 1 (Section 3.4) run on the GPU, for a matrix that is already in
+ * device memory (weights loaded there): row values per column block (Definition 3.2), the stable
+ * counting sort that yields the permutation (the bucket sort in the proof of Theorem 3.6), the full
+ * segmentation (Section 3.3) and the packing all happen on the device; the host only turns per-window
+ * entry counts into the schedule.  The handle is used exactly like one from rsr_preprocess and encodes
+ * the same index (rsr_export_block returns identical tables).  One difference in speed, none in
+ * results beyond float summation order: rsr_preprocess also orders the rows inside every group of
+ * equal rows so that the gathers spread over the LDS banks, which this call does not do.
+ *
+ *   A     DEVICE pointer, row-major rows x cols int8 in {-1,0,1}; read during the call only.
+ *   rows, cols, k   as for rsr_preprocess.
+ * Returns a handle, or NULL on error.  Synchronous; allocates temporary device memory of about
+ * 4 bytes per row and column block and part, plus 4 * 2^k bytes per column block and part.
+ */
+rsr_handle *rsr_preprocess_device(const int8_t *A, int64_t rows, int64_t cols, int k);
+
+/*
  * rsr_matvec - the RSR++ product (Section 4: segmented sums of Eq. SS2, then the fold of
  * Section 4.3 / Algorithm 3 per block; ternary result = (v . B(1)) - (v . B(2)),
  * Proposition 2.1), for float activations with float accumulation.

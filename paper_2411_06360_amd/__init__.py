@@ -36,4 +36,5 @@ from .binding import (  # noqa: F401
     RSR_STEP2_FOLD,
     RSR_STEP2_PLAIN,
     rsr_preprocess,
+    rsr_preprocess_device,
 )

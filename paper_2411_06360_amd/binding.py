@@ -81,6 +81,8 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
     L.rsr_preprocess.argtypes = [vp, i64, i64, ci]
     L.rsr_preprocess.restype = vp
+    L.rsr_preprocess_device.argtypes = [vp, i64, i64, ci]
+    L.rsr_preprocess_device.restype = vp
     L.rsr_matvec.argtypes = [vp, vp, vp, ci, vp]
     L.rsr_matvec.restype = ci
     L.rsr_matvec_i8.argtypes = [vp, vp, vp, ci, vp]
@@ -160,6 +162,14 @@ def rsr_preprocess(A, k: int) -> int:
     """``A``: host int8 array ``rows x cols``.  Returns the handle (an integer address)."""
     A = _host_matrix(A)
     h = load().rsr_preprocess(A.ctypes.data, A.shape[0], A.shape[1], int(k))
+    if not h:
+        raise RsrError(-1, rsr_last_error())
+    return int(h)
+
+
+def rsr_preprocess_device(A_dev, rows: int, cols: int, k: int) -> int:
+    """``A_dev``: device int8 buffer ``rows x cols`` (row-major).  Returns the handle."""
+    h = load().rsr_preprocess_device(_addr(A_dev), int(rows), int(cols), int(k))
     if not h:
         raise RsrError(-1, rsr_last_error())
     return int(h)

@@ -20,9 +20,7 @@
 
 #include "../../include/rsr_dense.h"
 
-namespace rsr_internal {
-int set_error(int code, const std::string& msg);  // rsr_lib.hip: the thread's message for rsr_last_error()
-}
+#include "rsr_internal.h"
 
 // Buffer of partial sums for rsr_dense_matvec_static: part of the code object, so every GPU the library
 // runs on holds its own copy at its own address from the moment the module is loaded there.  In host

@@ -64,6 +64,7 @@ constexpr int kFlagBytes1 = kLanes * 2;       // flags of positions 32..47 (only
 constexpr int kStreamAlign = 128;      // unit streams start on multiples of this
 constexpr int kMaxK = 16;
 constexpr int kMaxRows = 65534;        // 65535 values of uint16 minus the null index
+constexpr int64_t kTileRows = 32768;   // a matrix with more rows is indexed in row tiles of at most this height
 constexpr int kRecordWords = 16;       // per-unit result record in LDS: 9 low-bit sums, total, meta
 
 // bytes of a unit's stream before alignment

@@ -38,6 +38,7 @@
 
 #include "../../include/rsr.h"
 #include "rsr_format.h"
+#include "rsr_internal.h"
 #include "rsr_pack.h"
 
 namespace {
@@ -1018,6 +1019,58 @@ rsr_handle* rsr_preprocess(const int8_t* A, int64_t rows, int64_t cols, int k) {
     T.max_units_per_block = X.tiles[t].max_units_per_block;
     T.nunits = (int64_t)X.tiles[t].units.size();
     if (upload(&T, X.tiles[t]) != RSR_OK) { free_tables(h.get()); return nullptr; }
+  }
+  h->magic = kMagic;
+  return h.release();
+}
+
+rsr_handle* rsr_preprocess_device(const int8_t* A, int64_t rows, int64_t cols, int k) {
+  g_error.clear();
+  if (!A) { fail(RSR_ERR_INVALID_ARGUMENT, "rsr_preprocess_device: null pointer"); return nullptr; }
+  if (rows < 1 || rows > rsr::kMaxRows) { fail(RSR_ERR_INVALID_ARGUMENT, "rsr_preprocess_device: rows must be in 1..65534"); return nullptr; }
+  if (cols < 1) { fail(RSR_ERR_INVALID_ARGUMENT, "rsr_preprocess_device: cols must be >= 1"); return nullptr; }
+  if (k < 1 || k > rsr::kMaxK) { fail(RSR_ERR_INVALID_ARGUMENT, "rsr_preprocess_device: k must be in 1..16"); return nullptr; }
+  std::unique_ptr<rsr_handle> h(new (std::nothrow) rsr_handle());
+  if (!h) { fail(RSR_ERR_OUT_OF_MEMORY, "out of host memory"); return nullptr; }
+  hipError_t e = hipGetDevice(&h->device);
+  hipDeviceProp_t prop;
+  if (e == hipSuccess) e = hipGetDeviceProperties(&prop, h->device);
+  if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("rsr_preprocess_device: ") + hipGetErrorString(e)); return nullptr; }
+  h->num_cu = prop.multiProcessorCount;
+  h->lds_max = prop.sharedMemPerBlock;
+  std::string err;
+  int kind = 0;
+  int rc = rsr_internal::device_matrix_kind(A, rows * cols, &kind, &err);
+  if (rc != 0) { fail(rc, "rsr_preprocess_device: " + err); return nullptr; }
+  if (kind == 0) { fail(RSR_ERR_INVALID_ARGUMENT, "rsr_preprocess_device: an entry lies outside {-1,0,1}"); return nullptr; }
+  h->rows = rows; h->cols = cols; h->k = k; h->kw = std::min(k, rsr::kMaxWindowBits); h->parts = kind;
+  h->nblocks = (cols + k - 1) / k;
+  h->last_width = (int)(cols - (h->nblocks - 1) * k);
+  for (const void* kern : {reinterpret_cast<const void*>(rsr_matvec_kernel<float, false>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t, false>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<float, true>),
+                           reinterpret_cast<const void*>(rsr_matvec_kernel<int8_t, true>),
+                           reinterpret_cast<const void*>(rsr_multi_kernel<float>),
+                           reinterpret_cast<const void*>(rsr_multi_kernel<int8_t>)}) {
+    e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)h->lds_max);
+    if (e != hipSuccess) { (void)hipGetLastError(); fail(RSR_ERR_HIP, std::string("hipFuncSetAttribute: ") + hipGetErrorString(e)); return nullptr; }
+  }
+  const int64_t ntiles = (rows + rsr::kTileRows - 1) / rsr::kTileRows;
+  const int64_t height = ((rows + ntiles - 1) / ntiles + 15) / 16 * 16;
+  for (int64_t t = 0; t < ntiles; ++t) {
+    const int64_t r0 = t * height, r1 = std::min(rows, r0 + height);
+    rsr_internal::BuiltTile B;
+    rc = rsr_internal::device_build_tile(A + r0 * cols, r1 - r0, cols, cols, k, kind, &B, &err);
+    if (rc != 0) { free_tables(h.get()); fail(rc, "rsr_preprocess_device: " + err); return nullptr; }
+    DeviceTile T;
+    T.rows = r1 - r0; T.row0 = r0;
+    T.max_units_per_block = B.max_units_per_block; T.nunits = B.nunits;
+    T.stream_bytes = B.stream_bytes; T.unit_bytes = B.unit_bytes; T.blk_bytes = B.blk_bytes;
+    T.d_stream = B.d_stream; T.d_units = B.d_units; T.d_blk_unit = B.d_blk_unit;
+    h->tiles.push_back(T);
+    h->stored_rows += B.stored_rows; h->segments += B.segments; h->nunits += B.nunits;
+    h->flag_bytes += B.flag_bytes; h->stream_bytes += (int64_t)B.stream_bytes;
+    h->schedule_bytes += (int64_t)(B.unit_bytes + B.blk_bytes);
   }
   h->magic = kMagic;
   return h.release();

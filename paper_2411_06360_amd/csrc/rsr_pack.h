@@ -33,7 +33,6 @@ int pack_matrix(const int8_t* A, int64_t rows, int64_t cols, int k, int threads,
 
 // A matrix with more rows than kTileRows is indexed in row tiles of equal height (the product
 // is linear in the rows: the tiles' products add up).  Every tile is a packed index of its own.
-constexpr int64_t kTileRows = 32768;
 struct Index {
   int64_t rows = 0, cols = 0;
   std::vector<Packed> tiles;

@@ -431,6 +431,86 @@ def test_dense_bit_packed_comparator_against_the_oracle():
         R.rsr_dense_preprocess(np.full((2, 2), 3, np.int8))
 
 
+class DeviceBuiltIndex(DeviceIndex):
+    """An index built by rsr_preprocess_device from a matrix uploaded with torch."""
+
+    def __init__(self, A, k):
+        import time
+        import torch
+
+        dA = torch.from_numpy(np.ascontiguousarray(A)).cuda()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.handle = R.rsr_preprocess_device(dA, A.shape[0], A.shape[1], k)
+        self.seconds = time.perf_counter() - t0
+        self.info = R.rsr_info(self.handle)
+
+
+DEVICE_PREP = [
+    (6, 6, 2, "binary"), (50, 37, 3, "ternary"), (300, 64, 8, "binary"), (257, 100, 10, "ternary"), (1024, 48, 12, "binary"),
+    (700, 26, 13, "ternary"), (100, 33, 16, "ternary"), (40, 7, 1, "ternary"), (2000, 20, 5, "binary"), (40000, 7, 3, "ternary"),
+    (4000, 6, 3, "binary"), (3000, 24, 6, "zeros"), (5000, 40, 10, "skewed"),
+]
+
+
+@pytest.mark.parametrize("rows,cols,k,kind", DEVICE_PREP)
+def test_device_side_preprocess_builds_the_same_index(rows, cols, k, kind):
+    """Algorithm 1 on the GPU: the tables exported from the device-built index are the paper's sigma and L
+    (the oracle's, entry by entry), and its products are those of the host-built index."""
+    g = rng(rows * 11 + cols * 5 + k)
+    if kind == "binary":
+        A = g.integers(0, 2, size=(rows, cols)).astype(np.int8)
+    elif kind == "zeros":
+        A = np.zeros((rows, cols), np.int8)
+    elif kind == "skewed":
+        A = g.choice(np.array([-1, 0, 1], np.int8), size=(rows, cols), p=[0.15, 0.7, 0.15])
+    else:
+        A = g.integers(-1, 2, size=(rows, cols)).astype(np.int8)
+    note(f"device preprocess {rows}x{cols} k={k} {kind}")
+    parts = steps.ternary_split(A) if (A < 0).any() else (A,)
+    with DeviceBuiltIndex(A, k) as d, DeviceIndex(A, k) as hst:
+        assert d.info.parts == len(parts) == hst.info.parts and d.info.nblocks == hst.info.nblocks
+        assert d.info.stored_rows == hst.info.stored_rows and d.info.row_tiles == hst.info.row_tiles
+        for p_, Bp in enumerate(parts):
+            for b, Bi in enumerate(steps.column_blocks(Bp, k)):
+                if rows * (1 << Bi.shape[1]) > 40_000_000:
+                    continue  # (the oracle's L counts rows per value one by one)
+                sigma, L = R.rsr_export_block(d.handle, p_, b)
+                assert np.array_equal(sigma, steps.binary_row_order(Bi)), (p_, b)
+                assert np.array_equal(L[:-1], steps.full_segmentation(Bi)) and L[-1] == rows
+                s2, L2 = R.rsr_export_block(hst.handle, p_, b)
+                assert np.array_equal(sigma, s2) and np.array_equal(L, L2)
+        for batch in (1, 3):
+            v8 = g.integers(-127, 128, size=(batch, rows), dtype=np.int8)
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8))
+            vf = g.standard_normal((batch, rows)).astype(np.float32)
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf), vf)
+
+
+def test_device_side_preprocess_at_the_benchmark_configurations():
+    """Configurations 1 to 3 indexed on the device: product parity at full size, and the time Algorithm 1
+    takes on the GPU next to the host packer's."""
+    import time
+
+    for name in ("binary_1k", "ternary_4k", "binary_16k"):
+        w = workloads.get(name)
+        A = w.matrix()
+        t0 = time.perf_counter()
+        hx = R.rsr_host_pack(A, w.k)
+        host_s = time.perf_counter() - t0
+        R.rsr_host_free(hx)
+        with DeviceBuiltIndex(A, w.k) as d:
+            note(f"preprocess {name}: device {d.seconds * 1e3:.1f} ms, host packer {host_s * 1e3:.1f} ms; "
+                 f"device-built tables {d.info.table_bytes / 1e6:.2f} MB")
+            v8 = w.activations(1, "i8")
+            assert np.array_equal(d.matvec(v8).astype(np.int64), dense.matvec_i8(A, v8, threads=dense.host_threads()))
+            vf = w.activations(2, "f32")
+            assert_f32_close(d.matvec(vf), dense.matvec_f32(A, vf, threads=dense.host_threads()), vf)
+            sigma, L = R.rsr_export_block(d.handle, 0, 3)
+            Bi = steps.column_blocks(steps.ternary_split(A)[0] if (A < 0).any() else A, w.k)[3]
+            assert np.array_equal(sigma, steps.binary_row_order(Bi))
+
+
 def test_unaligned_activation_pointer_and_odd_row_count():
     import torch
 
