@@ -63,6 +63,9 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="budget of the CPU-oracle timing leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg and with it the parity check (profiling runs)")
     ap.add_argument("--no-check", action="store_true", help="skip the parity check against the CPU leg's product")
+    ap.add_argument("--plain", action="store_true",
+                    help="only the W warm-up and K timed steps: no conditioning launches, no per-group spread, no warm figure "
+                         "(for runs under a profiler, where every launch of the process is counted)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="N",
                     help="also run N plain device copies of 256 MiB (a kernel of known traffic, used to "
                          "scale the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -315,8 +318,9 @@ def main():
 
     # Untimed conditioning before the W warm-up steps: the same product for a few tens of milliseconds, so that
     # a short timed region (the default driver run times 20 steps) sees the device at its steady clock.
-    run(PRECONDITION_LAUNCHES)
-    torch.cuda.synchronize()
+    if not args.plain:
+        run(PRECONDITION_LAUNCHES)
+        torch.cuda.synchronize()
     run(args.warmup)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -338,25 +342,27 @@ def main():
         del src, dst
 
     # ---- spread of the launch duration (groups of ten launches, cold rotation continues) and the warm figure
-    group, ngroups = 10, max(5, min(100, args.steps // 10))
-    evs = [torch.cuda.Event(enable_timing=True) for _ in range(ngroups + 1)]
-    evs[0].record()
-    for gi in range(ngroups):
-        run(group, args.warmup + args.steps + gi * group)
-        evs[gi + 1].record()
-    torch.cuda.synchronize()
-    per_group = sorted(evs[gi].elapsed_time(evs[gi + 1]) * 1e3 / group for gi in range(ngroups))
-    wsteps = max(20, min(args.steps, 1000))
-    for _ in range(20):
-        fn(handles[0], pv, po, args.batch, stream)
-    torch.cuda.synchronize()
-    w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    w0.record()
-    for _ in range(wsteps):
-        fn(handles[0], pv, po, args.batch, stream)
-    w1.record()
-    torch.cuda.synchronize()
-    warm_us = w0.elapsed_time(w1) * 1e3 / wsteps
+    per_group, warm_us = [None], None
+    if not args.plain:
+        group, ngroups = 10, max(5, min(100, args.steps // 10))
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(ngroups + 1)]
+        evs[0].record()
+        for gi in range(ngroups):
+            run(group, args.warmup + args.steps + gi * group)
+            evs[gi + 1].record()
+        torch.cuda.synchronize()
+        per_group = sorted(evs[gi].elapsed_time(evs[gi + 1]) * 1e3 / group for gi in range(ngroups))
+        wsteps = max(20, min(args.steps, 1000))
+        for _ in range(20):
+            fn(handles[0], pv, po, args.batch, stream)
+        torch.cuda.synchronize()
+        w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0.record()
+        for _ in range(wsteps):
+            fn(handles[0], pv, po, args.batch, stream)
+        w1.record()
+        torch.cuda.synchronize()
+        warm_us = w0.elapsed_time(w1) * 1e3 / wsteps
 
     ms_per_step = wall * 1e3 / args.steps
     launch_us = dev_ms * 1e3 / args.steps
@@ -386,7 +392,7 @@ def main():
             "regime": args.regime,
             "step2": args.step2,
             "index_copies_rotated": ncopies,
-            "untimed_conditioning_launches": PRECONDITION_LAUNCHES,
+            "untimed_conditioning_launches": 0 if args.plain else PRECONDITION_LAUNCHES,
             "working_set_bytes": ncopies * table_bytes,
             "table_bytes": table_bytes,
             "stored_rows": int(info.stored_rows),
