@@ -145,6 +145,22 @@ int rsr_matvec_multi(const rsr_job *jobs, int njobs, int batch, void *stream);
 int rsr_matvec_multi_i8(const rsr_job *jobs, int njobs, int batch, void *stream);
 
 /*
+ * rsr_matvec_acc / rsr_matvec_acc_i8 - out += scale * (v . A): the product of rsr_matvec, scaled,
+ * added to what `out` holds instead of replacing it.  This is the combining step of a weighted sum
+ * of binary or ternary matrices, which is how Proposition 2.1 builds a ternary product from two
+ * binary ones and how Appendix "Generalization" extends the method to matrices with more bits per
+ * entry (rsr_qbit.h does that with these calls).
+ *   v, out, batch, stream   as for rsr_matvec / rsr_matvec_i8; `out` must hold valid numbers
+ *   scale                   finite float; any int32 for _i8 (the caller keeps the sums within int32)
+ * Float: out[c] = out[c] + scale * p[c], with p the product as rsr_matvec computes it (rounded),
+ * then one fused multiply-add or a rounded multiplication and a rounded addition.  int8: exact.
+ * Asynchronous, allocates nothing.
+ * Errors as rsr_matvec; RSR_ERR_INVALID_ARGUMENT for a scale that is not finite.
+ */
+int rsr_matvec_acc(rsr_handle *h, const float *v, float *out, float scale, int batch, void *stream);
+int rsr_matvec_acc_i8(rsr_handle *h, const int8_t *v, int32_t *out, int32_t scale, int batch, void *stream);
+
+/*
  * rsr_set_step2 - which form of step 2 (the product of the segmented sums u with Bin_[k]) later
  * rsr_matvec / rsr_matvec_i8 calls on this handle use:
  *   RSR_STEP2_FOLD   the RSR++ halving fold of Section 4.3 / Algorithm 3, O(2^k) (the default);

@@ -46,7 +46,7 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-def _prep(A: np.ndarray, v: np.ndarray, vdtype):
+def _prep(A: np.ndarray, v: np.ndarray, vdtype, qbits: Optional[int] = None):
     A = np.ascontiguousarray(A, dtype=np.int8)
     if A.ndim != 2:
         raise ValueError("A must be 2-D (rows x cols)")
@@ -56,18 +56,27 @@ def _prep(A: np.ndarray, v: np.ndarray, vdtype):
         v = v[None, :]
     if v.ndim != 2 or v.shape[1] != A.shape[0]:
         raise ValueError(f"v must be [batch][rows={A.shape[0]}], got {v.shape}")
-    bad = lib().rsr_oracle_check_entries(A.ctypes.data_as(_i8p), A.shape[0], A.shape[1])
-    if bad:
-        raise ValueError(f"A has an entry outside {{-1,0,1}} at flat index {bad - 1}")
+    if qbits is None:
+        bad = lib().rsr_oracle_check_entries(A.ctypes.data_as(_i8p), A.shape[0], A.shape[1])
+        if bad:
+            raise ValueError(f"A has an entry outside {{-1,0,1}} at flat index {bad - 1}")
+    else:
+        # a matrix with q bits per entry (appendix "Generalization"): the same definition of the
+        # product, entries in the two's complement range of q bits
+        lo, hi = -(1 << (qbits - 1)), (1 << (qbits - 1)) - 1
+        if not 2 <= qbits <= 8 or A.min() < lo or A.max() > hi:
+            raise ValueError(f"A has an entry outside {lo}..{hi}, or q is not in 2..8")
     return A, v, squeeze
 
 
-def matvec_f32(A: np.ndarray, v: np.ndarray, threads: int = 1, cols: Optional[tuple] = None) -> np.ndarray:
+def matvec_f32(A: np.ndarray, v: np.ndarray, threads: int = 1, cols: Optional[tuple] = None,
+               qbits: Optional[int] = None) -> np.ndarray:
     """float activations -> float64 result ``[batch][cols]`` (or ``[cols]`` for a 1-D ``v``).
 
     ``cols=(c0, c1)`` computes only that column range; the other outputs are NaN.
+    ``qbits=q`` admits entries of q bits (two's complement) instead of {-1,0,1}.
     """
-    A, v, squeeze = _prep(A, v, np.float32)
+    A, v, squeeze = _prep(A, v, np.float32, qbits)
     rows, ncols = A.shape
     out = np.full((v.shape[0], ncols), np.nan, dtype=np.float64)
     a, vp, op = A.ctypes.data_as(_i8p), v.ctypes.data_as(_f32p), out.ctypes.data_as(_f64p)
@@ -81,12 +90,14 @@ def matvec_f32(A: np.ndarray, v: np.ndarray, threads: int = 1, cols: Optional[tu
     return out[0] if squeeze else out
 
 
-def matvec_i8(A: np.ndarray, v: np.ndarray, threads: int = 1, cols: Optional[tuple] = None) -> np.ndarray:
+def matvec_i8(A: np.ndarray, v: np.ndarray, threads: int = 1, cols: Optional[tuple] = None,
+              qbits: Optional[int] = None) -> np.ndarray:
     """int8 activations -> int64 result ``[batch][cols]`` (or ``[cols]`` for a 1-D ``v``).
 
     ``cols=(c0, c1)`` computes only that column range; the other outputs are left at int64 min.
+    ``qbits=q`` admits entries of q bits (two's complement) instead of {-1,0,1}.
     """
-    A, v, squeeze = _prep(A, v, np.int8)
+    A, v, squeeze = _prep(A, v, np.int8, qbits)
     rows, ncols = A.shape
     out = np.full((v.shape[0], ncols), np.iinfo(np.int64).min, dtype=np.int64)
     a, vp, op = A.ctypes.data_as(_i8p), v.ctypes.data_as(_i8p), out.ctypes.data_as(_i64p)

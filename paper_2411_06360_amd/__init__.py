@@ -21,6 +21,14 @@ from .binding import (  # noqa: F401
     rsr_last_error,
     rsr_matvec,
     rsr_matvec_i8,
+    rsr_matvec_acc,
+    rsr_matvec_acc_i8,
+    rsr_qbit_preprocess,
+    rsr_qbit_matvec,
+    rsr_qbit_matvec_i8,
+    rsr_qbit_planes,
+    rsr_qbit_table_bytes,
+    rsr_qbit_destroy,
     rsr_matvec_multi,
     rsr_matvec_multi_i8,
     make_jobs,

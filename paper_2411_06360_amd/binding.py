@@ -116,6 +116,22 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     L.rsr_host_streams.argtypes = ([vp, ci] + [ctypes.POINTER(vp), ctypes.POINTER(i64)] * 2 + [ctypes.POINTER(vp)]
                                    + [ctypes.POINTER(i64)] * 2)
     L.rsr_host_streams.restype = ci
+    L.rsr_matvec_acc.argtypes = [vp, vp, vp, ctypes.c_float, ci, vp]
+    L.rsr_matvec_acc.restype = ci
+    L.rsr_matvec_acc_i8.argtypes = [vp, vp, vp, ctypes.c_int32, ci, vp]
+    L.rsr_matvec_acc_i8.restype = ci
+    L.rsr_qbit_preprocess.argtypes = [vp, i64, i64, ci, ci]
+    L.rsr_qbit_preprocess.restype = vp
+    L.rsr_qbit_matvec.argtypes = [vp, vp, vp, ci, vp]
+    L.rsr_qbit_matvec.restype = ci
+    L.rsr_qbit_matvec_i8.argtypes = [vp, vp, vp, ci, vp]
+    L.rsr_qbit_matvec_i8.restype = ci
+    L.rsr_qbit_planes.argtypes = [vp]
+    L.rsr_qbit_planes.restype = ci
+    L.rsr_qbit_table_bytes.argtypes = [vp]
+    L.rsr_qbit_table_bytes.restype = i64
+    L.rsr_qbit_destroy.argtypes = [vp]
+    L.rsr_qbit_destroy.restype = None
     L.rsr_dense_preprocess.argtypes = [vp, i64, i64]
     L.rsr_dense_preprocess.restype = vp
     L.rsr_dense_matvec.argtypes = [vp, vp, vp, ci, vp]
@@ -183,6 +199,46 @@ def rsr_matvec(handle: int, v, out, batch: int, stream=None) -> None:
 def rsr_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
     """``v``: device int8 ``[batch][rows]``; ``out``: device int32 ``[batch][cols]``."""
     _check(load().rsr_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_matvec_acc(handle: int, v, out, scale: float, batch: int, stream=None) -> None:
+    """``out += scale * (v . A)`` on device float32 buffers."""
+    _check(load().rsr_matvec_acc(handle, _addr(v), _addr(out), float(scale), int(batch), _addr(stream)))
+
+
+def rsr_matvec_acc_i8(handle: int, v, out, scale: int, batch: int, stream=None) -> None:
+    """``out += scale * (v . A)`` for device int8 activations and int32 results."""
+    _check(load().rsr_matvec_acc_i8(handle, _addr(v), _addr(out), int(scale), int(batch), _addr(stream)))
+
+
+# ---- q-bit matrices as weighted binary planes (include/rsr_qbit.h) ----
+def rsr_qbit_preprocess(A, k: int, q: int) -> int:
+    A = _host_matrix(A)
+    h = load().rsr_qbit_preprocess(A.ctypes.data, A.shape[0], A.shape[1], int(k), int(q))
+    if not h:
+        raise RsrError(-1, rsr_last_error())
+    return int(h)
+
+
+def rsr_qbit_matvec(handle: int, v, out, batch: int, stream=None) -> None:
+    _check(load().rsr_qbit_matvec(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_qbit_matvec_i8(handle: int, v, out, batch: int, stream=None) -> None:
+    _check(load().rsr_qbit_matvec_i8(handle, _addr(v), _addr(out), int(batch), _addr(stream)))
+
+
+def rsr_qbit_planes(handle: int) -> int:
+    return int(load().rsr_qbit_planes(handle))
+
+
+def rsr_qbit_table_bytes(handle: int) -> int:
+    return int(load().rsr_qbit_table_bytes(handle))
+
+
+def rsr_qbit_destroy(handle: Optional[int]) -> None:
+    if handle:
+        load().rsr_qbit_destroy(handle)
 
 
 RSR_STEP2_FOLD, RSR_STEP2_PLAIN = 0, 1

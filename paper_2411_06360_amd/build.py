@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsr.so")
-SOURCES = ["rsr_lib.hip", "rsr_dense.hip", "rsr_prep.hip", "rsr_pack.cpp"]
+SOURCES = ["rsr_lib.hip", "rsr_dense.hip", "rsr_prep.hip", "rsr_pack.cpp", "rsr_qbit.cpp"]
 ARCH = "gfx950"
 
 # -packed-fp32-ops off: the compiler must not form packed fp32 instructions from the float adds.

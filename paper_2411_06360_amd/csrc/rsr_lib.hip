@@ -136,7 +136,9 @@ struct KArgs {
   int rows, cols, k, kw, parts, nblocks, last_width, batch;
   int vstride;   // elements between the activation vectors of consecutive batch lanes (the matrix's row count)
   int row0;      // first row of this row tile
-  int accumulate;  // add to `out` instead of overwriting it (second and later row tiles)
+  int accumulate;  // add to `out` instead of overwriting it (second and later row tiles, rsr_matvec_acc)
+  int scaled;      // multiply the product by `scale` first (rsr_matvec_acc)
+  uint32_t scale;  // bits of a float (float activations) or of an int (int8 activations)
   int g1;        // workgroups per batch lane
   int waves;     // wavefronts that take units (the LDS layout has a window for each)
   int ucap;      // unit records per round
@@ -715,7 +717,8 @@ __device__ __forceinline__ void rsr_body(const unsigned char* __restrict__ strea
         const int col = p.k - 1 - bit;
         if (lane < 16 && bit < p.k && col < width) {
           AT* dst = outp + (int64_t)D.block * p.k + col;
-          *dst = p.accumulate ? *dst + res : res;  // row tiles add up: the product is linear in the rows
+          const AT term = p.scaled ? res * __builtin_bit_cast(AT, p.scale) : res;
+          *dst = p.accumulate ? *dst + term : term;  // row tiles add up: the product is linear in the rows
         }
       }
       ix = ix1; D = D1;
@@ -855,10 +858,11 @@ int plan_tile(const rsr_handle* h, const DeviceTile& T, bool accumulate, int bat
 }
 
 template <typename VT>
-int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const VT* v, void* out, int batch, void* stream) {
+int launch_tile(rsr_handle* h, const DeviceTile& T, bool accumulate, const uint32_t* scale, const VT* v, void* out, int batch, void* stream) {
   LaunchPlan plan;
   const int rc = plan_tile<VT>(h, T, accumulate, batch, h->num_cu, 4, &plan);
   if (rc != RSR_OK) return rc;
+  if (scale) { plan.p.scaled = 1; plan.p.scale = *scale; }
   auto kern = h->step2_plain ? rsr_matvec_kernel<VT, true> : rsr_matvec_kernel<VT, false>;
   hipLaunchKernelGGL(kern, dim3((unsigned)plan.grid), dim3((unsigned)(plan.waves * 64)), plan.lds, static_cast<hipStream_t>(stream),
                      static_cast<const unsigned char*>(T.d_stream), static_cast<const uint32_t*>(T.d_units), static_cast<const uint32_t*>(T.d_blk_unit), v,
@@ -934,13 +938,14 @@ int launch_multi(const rsr_job* jobs, int njobs, int batch, void* stream) {
 
 // One launch per row tile, in order, on the caller's stream: the first overwrites `out`, the others add.
 template <typename VT>
-int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream) {
+// With `scale` (rsr_matvec_acc) every launch adds scale * (its tile's product) to `out`.
+int launch(rsr_handle* h, const VT* v, void* out, int batch, void* stream, const uint32_t* scale = nullptr) {
   if (!valid(h)) return fail(RSR_ERR_INVALID_ARGUMENT, "invalid handle");
   if (!v || !out) return fail(RSR_ERR_INVALID_ARGUMENT, "null pointer");
   if (batch < 1) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be >= 1");
   if (batch > 65535) return fail(RSR_ERR_INVALID_ARGUMENT, "batch must be <= 65535");
   for (size_t t = 0; t < h->tiles.size(); ++t) {
-    const int rc = launch_tile<VT>(h, h->tiles[t], t > 0, v, out, batch, stream);
+    const int rc = launch_tile<VT>(h, h->tiles[t], t > 0 || scale != nullptr, scale, v, out, batch, stream);
     if (rc != RSR_OK) return rc;
   }
   return RSR_OK;
@@ -1082,6 +1087,17 @@ int rsr_matvec(rsr_handle* h, const float* v, float* out, int batch, void* strea
 
 int rsr_matvec_i8(rsr_handle* h, const int8_t* v, int32_t* out, int batch, void* stream) {
   return launch<int8_t>(h, v, out, batch, stream);
+}
+
+int rsr_matvec_acc(rsr_handle* h, const float* v, float* out, float scale, int batch, void* stream) {
+  if (!(scale == scale) || scale - scale != 0.0f) return fail(RSR_ERR_INVALID_ARGUMENT, "rsr_matvec_acc: scale must be finite");
+  const uint32_t bits = __builtin_bit_cast(uint32_t, scale);
+  return launch<float>(h, v, out, batch, stream, &bits);
+}
+
+int rsr_matvec_acc_i8(rsr_handle* h, const int8_t* v, int32_t* out, int32_t scale, int batch, void* stream) {
+  const uint32_t bits = (uint32_t)scale;
+  return launch<int8_t>(h, v, out, batch, stream, &bits);
 }
 
 int rsr_matvec_multi(const rsr_job* jobs, int njobs, int batch, void* stream) {

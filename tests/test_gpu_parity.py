@@ -453,6 +453,66 @@ DEVICE_PREP = [
 ]
 
 
+# ---- out += scale * (v . A), and matrices with q bits per entry as weighted binary planes ---------------
+def test_scaled_accumulation_into_the_result():
+    import torch
+
+    g = rng(151)
+    A = g.integers(-1, 2, size=(1500, 333)).astype(np.int8)
+    v8 = g.integers(-128, 128, size=(3, 1500), dtype=np.int8)
+    vf = g.standard_normal((3, 1500)).astype(np.float32)
+    st = torch.cuda.current_stream().cuda_stream
+    with DeviceIndex(A, 9) as d:
+        start8 = g.integers(-1000, 1000, size=(3, 333)).astype(np.int32)
+        o8 = torch.from_numpy(start8.copy()).cuda()
+        R.rsr_matvec_acc_i8(d.handle, torch.from_numpy(v8).cuda(), o8, -5, 3, st)
+        R.rsr_matvec_acc_i8(d.handle, torch.from_numpy(v8).cuda(), o8, 1, 3, st)
+        torch.cuda.synchronize()
+        assert np.array_equal(o8.cpu().numpy().astype(np.int64), start8 - 4 * dense.matvec_i8(A, v8))
+        startf = g.standard_normal((3, 333)).astype(np.float32)
+        of = torch.from_numpy(startf.copy()).cuda()
+        R.rsr_matvec_acc(d.handle, torch.from_numpy(vf).cuda(), of, 0.375, 3, st)
+        torch.cuda.synchronize()
+        want = startf.astype(np.float64) + 0.375 * dense.matvec_f32(A, vf)
+        assert_f32_close(of.cpu().numpy(), want, vf)   # |scale| < 1: the bound of the plain product covers it
+        with pytest.raises(R.RsrError):
+            R.rsr_matvec_acc(d.handle, torch.from_numpy(vf).cuda(), of, float("inf"), 3, st)
+
+
+@pytest.mark.parametrize("q,rows,cols,k", [(2, 700, 130, 8), (4, 2100, 257, 10), (8, 1024, 96, 8), (3, 40000, 40, 10)])
+def test_qbit_matrix_as_weighted_binary_planes(q, rows, cols, k):
+    import torch
+
+    g = rng(160 + q)
+    lo, hi = -(1 << (q - 1)), (1 << (q - 1)) - 1
+    A = g.integers(lo, hi + 1, size=(rows, cols)).astype(np.int8)
+    A[0, 0], A[1, 0] = lo, hi
+    batch = 2
+    v8 = g.integers(-128, 128, size=(batch, rows), dtype=np.int8)
+    vf = g.standard_normal((batch, rows)).astype(np.float32)
+    st = torch.cuda.current_stream().cuda_stream
+    note(f"q-bit q={q} {rows}x{cols} k={k}")
+    h = R.rsr_qbit_preprocess(A, k, q)
+    try:
+        assert R.rsr_qbit_planes(h) == q and R.rsr_qbit_table_bytes(h) > 0
+        o8 = torch.full((batch, cols), -7, dtype=torch.int32, device="cuda")
+        R.rsr_qbit_matvec_i8(h, torch.from_numpy(v8).cuda(), o8, batch, st)
+        of = torch.full((batch, cols), float("nan"), dtype=torch.float32, device="cuda")
+        R.rsr_qbit_matvec(h, torch.from_numpy(vf).cuda(), of, batch, st)
+        torch.cuda.synchronize()
+        assert np.array_equal(o8.cpu().numpy().astype(np.int64), dense.matvec_i8(A, v8, qbits=q))
+        # q planes, each within 1e-5 * sum|v| of its exact product, weights 2^i: together below 2^q * 1e-5 * sum|v|;
+        # the stated bound is half of that
+        assert_f32_close(of.cpu().numpy(), dense.matvec_f32(A, vf, qbits=q), vf, rel=1e-5 * (1 << (q - 1)))
+    finally:
+        torch.cuda.synchronize()
+        R.rsr_qbit_destroy(h)
+    with pytest.raises(R.RsrError):
+        R.rsr_qbit_preprocess(np.full((4, 4), 2, np.int8), 2, 2)   # 2 does not fit in 2 bits
+    with pytest.raises(R.RsrError):
+        R.rsr_qbit_preprocess(A, k, 9)
+
+
 @pytest.mark.parametrize("rows,cols,k,kind", DEVICE_PREP)
 def test_device_side_preprocess_builds_the_same_index(rows, cols, k, kind):
     """Algorithm 1 on the GPU: the tables exported from the device-built index are the paper's sigma and L

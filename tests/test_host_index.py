@@ -53,6 +53,12 @@ def test_library_exports_every_declared_symbol():
     assert {"rsr_dense_preprocess", "rsr_dense_matvec", "rsr_dense_matvec_i8", "rsr_dense_destroy"} <= dnames
     for n in sorted(dnames):
         assert hasattr(lib, n), f"{n} declared in rsr_dense.h but not exported"
+    qbit_h = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "rsr_qbit.h")).read(), flags=re.S)
+    qnames = set(re.findall(r"\b(rsr_qbit_[a-z0-9_]+)\s*\(", qbit_h))
+    assert {"rsr_qbit_preprocess", "rsr_qbit_matvec", "rsr_qbit_matvec_i8", "rsr_qbit_destroy"} <= qnames
+    assert {"rsr_matvec_acc", "rsr_matvec_acc_i8"} <= names
+    for n in sorted(qnames):
+        assert hasattr(lib, n), f"{n} declared in rsr_qbit.h but not exported"
 
 
 def test_block_width_by_the_papers_cost_formula():

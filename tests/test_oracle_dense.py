@@ -187,3 +187,33 @@ def test_rejects_entries_outside_the_ternary_set():
     A[2, 1] = 2
     with pytest.raises(ValueError):
         dense.matvec_i8(A, np.ones(4, np.int8))
+
+
+# ---- entries with q bits (appendix "Generalization") -------------------------------------
+@pytest.mark.parametrize("q", [2, 3, 4, 8])
+def test_qbit_entries_against_numpy_and_against_the_weighted_bit_planes(q):
+    g = rng(600 + q)
+    lo, hi = -(1 << (q - 1)), (1 << (q - 1)) - 1
+    A = g.integers(lo, hi + 1, size=(300, 77)).astype(np.int8)
+    A[0, 0], A[1, 0] = lo, hi
+    v8 = g.integers(-127, 128, size=(2, 300), dtype=np.int8)
+    v8[0, :2] = (-128, 127)
+    got = dense.matvec_i8(A, v8, qbits=q)
+    assert np.array_equal(got, v8.astype(np.int64) @ A.astype(np.int64))   # library routine, second opinion
+    # the decomposition the appendix describes, written out with two's complement bit planes:
+    # A = sum_{i<q-1} 2^i B_i - 2^(q-1) B_{q-1}, every B_i binary and multiplied on its own
+    planes = [((A.astype(np.uint8) >> i) & 1).astype(np.int8) for i in range(q)]
+    assert np.array_equal(sum((-(1 << i) if i == q - 1 else (1 << i)) * P.astype(np.int64) for i, P in enumerate(planes)), A)
+    combined = sum((-(1 << i) if i == q - 1 else (1 << i)) * dense.matvec_i8(P, v8) for i, P in enumerate(planes))
+    assert np.array_equal(got, combined)
+    vf = g.standard_normal((2, 300)).astype(np.float32)
+    ref = vf.astype(np.float64) @ A.astype(np.float64)
+    assert np.all(np.abs(dense.matvec_f32(A, vf, qbits=q) - ref) <= 1e-12 * (1 << q) * np.abs(vf).sum(axis=1, keepdims=True))
+
+
+def test_qbit_rejects_entries_outside_the_range():
+    A = np.zeros((4, 4), np.int8)
+    A[3, 3] = 2
+    with pytest.raises(ValueError):
+        dense.matvec_i8(A, np.ones(4, np.int8), qbits=2)
+    assert dense.matvec_i8(A, np.ones(4, np.int8), qbits=3)[3] == 2
