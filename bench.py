@@ -42,6 +42,10 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 # holds the stored table bytes of the build that was profiled, and the figure is reported only while
 # the tables still have that size (any change of the layout makes it null until it is measured again).
 PROFILED_TRAFFIC = {
+    ("binary_16k", 1, "f32", "cold"): {"table_bytes": 49610972, "traffic_bytes": 51.03e6,
+                                       "source": "profiles/rsr_matvec_f32_binary16k_b1_cold.md"},
+    ("binary_16k", 8, "f32", "cold"): {"table_bytes": 49610972, "traffic_bytes": 58.43e6,
+                                       "source": "profiles/rsr_matvec_f32_binary16k_b8_cold.md"},
 }
 PRECONDITION_LAUNCHES = 3000   # untimed, before the warm-up steps (see main)
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache; the cold regime rotates over > 2x this

@@ -123,13 +123,28 @@ dense_partial_kernel(const uint32_t* __restrict__ bits, const VT* __restrict__ v
   }
 }
 
+// Sum of the row tiles' partial results, in a fixed order: a workgroup of 256 threads owns 64
+// outputs; thread (q, j) adds the tiles q, q+4, q+8, ... of output j (independent loads, all in
+// flight together), and the four quarter sums are added in order through LDS.
 template <typename AT>
-__global__ void dense_reduce_kernel(const AT* __restrict__ partial, AT* __restrict__ out, int ntiles, int64_t n) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  AT s = partial[i];
-  for (int t = 1; t < ntiles; ++t) s += partial[(int64_t)t * n + i];
-  out[i] = s;
+__global__ void __launch_bounds__(256) dense_reduce_kernel(const AT* __restrict__ partial, AT* __restrict__ out, int ntiles, int64_t n) {
+  __shared__ AT quarter[4][64];
+  const int j = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int64_t i = (int64_t)blockIdx.x * 64 + j;
+  AT s = (AT)0;
+  if (i < n) {
+    AT s0 = (AT)0, s1 = (AT)0;
+    int t = q;
+    for (; t + 4 < ntiles; t += 8) {
+      s0 += partial[(int64_t)t * n + i];
+      s1 += partial[(int64_t)(t + 4) * n + i];
+    }
+    if (t < ntiles) s0 += partial[(int64_t)t * n + i];
+    s = s0 + s1;
+  }
+  quarter[q][j] = s;
+  __syncthreads();
+  if (q == 0 && i < n) out[i] = (quarter[0][j] + quarter[1][j]) + (quarter[2][j] + quarter[3][j]);
 }
 
 }  // namespace
@@ -164,7 +179,7 @@ int dense_launch(rsr_dense* h, const VT* v, void* out, int batch, void* stream, 
   hipLaunchKernelGGL(kern, grid, dim3(kColsPerWg), 0, st, static_cast<const uint32_t*>(h->d_bits), v,
                      static_cast<AT*>(scratch), (int)h->rows, (int)h->cols, (int)h->cols_pad, (int)h->nchunks, batch);
   const int64_t n = (int64_t)batch * h->cols;
-  hipLaunchKernelGGL(dense_reduce_kernel<AT>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, static_cast<const AT*>(scratch),
+  hipLaunchKernelGGL(dense_reduce_kernel<AT>, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, st, static_cast<const AT*>(scratch),
                      static_cast<AT*>(out), h->ntiles, n);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return rsr_internal::set_error(RSR_ERR_HIP, std::string("dense launch: ") + hipGetErrorString(e));
