@@ -130,26 +130,28 @@ def bench_llm_block(args):
     mats = [workloads.stage_matrix(members) for _, members in stages]
     k = stages[0][1][0].k
     batch = args.batch
-    vs = [members[0].activations(batch, "f32") for _, members in stages]
+    i8 = args.dtype == "i8"   # the int8 activations of a BitLinear-style layer (Section 5.3), int32 results, exact
+    vs = [members[0].activations(batch, args.dtype) for _, members in stages]
     first = [R.rsr_preprocess(A, k) for A in mats]
     infos = [R.rsr_info(h) for h in first]
     table_bytes = sum(int(i.table_bytes) for i in infos)
     ncopies = 1 if args.regime == "warm" else min(32, max(2, -(-2 * LLC_BYTES // table_bytes) + 1))
     copies = [first] + [[R.rsr_preprocess(A, k) for A in mats] for _ in range(ncopies - 1)]
     dv = [torch.from_numpy(v).cuda() for v in vs]
-    outs = [torch.zeros((batch, A.shape[1]), dtype=torch.float32, device="cuda") for A in mats]
+    outs = [torch.zeros((batch, A.shape[1]), dtype=torch.int32 if i8 else torch.float32, device="cuda") for A in mats]
     lib = R.load()
+    matvec = lib.rsr_matvec_i8 if i8 else lib.rsr_matvec
     cur = torch.cuda.current_stream().cuda_stream
 
     def launches(hs, stream):
         for h, v, o in zip(hs, dv, outs):
-            if lib.rsr_matvec(h, v.data_ptr(), o.data_ptr(), batch, stream) != 0:
+            if matvec(h, v.data_ptr(), o.data_ptr(), batch, stream) != 0:
                 raise RuntimeError(R.rsr_last_error())
 
     jobs = [R.make_jobs(list(zip(hs, dv, outs))) for hs in copies]
 
     def fused(c, stream):
-        R.rsr_matvec_multi(jobs[c], batch, stream)
+        (R.rsr_matvec_multi_i8 if i8 else R.rsr_matvec_multi)(jobs[c], batch, stream)
 
     launches(copies[-1], cur)
     torch.cuda.synchronize()
@@ -189,11 +191,11 @@ def bench_llm_block(args):
     per_stage = []
     for si in range(len(stages)):
         def one(c, si=si):
-            if lib.rsr_matvec(copies[c][si], dv[si].data_ptr(), outs[si].data_ptr(), batch, cur) != 0:
+            if matvec(copies[c][si], dv[si].data_ptr(), outs[si].data_ptr(), batch, cur) != 0:
                 raise RuntimeError(R.rsr_last_error())
         per_stage.append(timed(one, args.steps, args.warmup)[1])
 
-    io_bytes = sum(batch * (A.shape[0] * 4 + A.shape[1] * 4) for A in mats)
+    io_bytes = sum(batch * (A.shape[0] * (1 if i8 else 4) + A.shape[1] * 4) for A in mats)
     method_bytes = sum(int(i.parts) * int(i.nblocks) * (int(i.rows) * 2 + (1 << k) * 2) for i in infos) + io_bytes
     stored_bytes = table_bytes + io_bytes
     result = {
@@ -202,9 +204,9 @@ def bench_llm_block(args):
         "unit": "blocks/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {
-            "workload": f"llm_block: stages {[n for n, _ in stages]} with shapes {[list(A.shape) for A in mats]}, k={k}, batch {batch}, f32 activations",
+            "workload": f"llm_block: stages {[n for n, _ in stages]} with shapes {[list(A.shape) for A in mats]}, k={k}, batch {batch}, {args.dtype} activations",
             "regime": args.regime, "index_copies_rotated": ncopies, "table_bytes": table_bytes,
             "step": "four launches captured in one HIP graph, one replay per step",
             "us_per_block_graph": graph_us, "us_per_block_four_launches": plain_us, "us_per_block_one_launch": fused_us,
@@ -222,9 +224,15 @@ def bench_llm_block(args):
     }
     if not args.no_cpu:
         threads = dense.host_threads()
-        exact = [dense.matvec_f32(A, v, threads=threads) for A, v in zip(mats, vs)]
+        oracle_fn = dense.matvec_i8 if i8 else dense.matvec_f32
+        exact = [oracle_fn(A, v, threads=threads) for A, v in zip(mats, vs)]
         worst = 0.0
         for g_, e_, v in zip(got, exact, vs):
+            if i8:
+                if not np.array_equal(g_.astype(np.int64), e_):
+                    print("parity FAILED: int8 result differs from the oracle", file=sys.stderr)
+                    sys.exit(1)
+                continue
             bound = 1e-5 * np.abs(v.astype(np.float64)).sum(axis=1, keepdims=True)
             worst = max(worst, float((np.abs(g_.astype(np.float64) - e_) / bound).max()))
         if not worst <= 1.0:
@@ -235,7 +243,7 @@ def bench_llm_block(args):
         reps = 0
         while time.perf_counter() - t0 < args.cpu_seconds:
             for A, v in zip(mats, vs):
-                dense.matvec_f32(A, v[:1], threads=threads)
+                oracle_fn(A, v[:1], threads=threads)
             reps += 1
         result["cpu_baseline"] = {
             "value": reps / (time.perf_counter() - t0), "unit": "blocks/s", "cores": threads, "kind": "oracle",

@@ -453,6 +453,56 @@ DEVICE_PREP = [
 ]
 
 
+# ---- seeded random cases: shapes, k, value laws, batch sizes drawn at random ------------------------------
+def test_random_cases_against_the_oracle():
+    """40 seeded cases over odd shapes (1 .. 20000 rows, 1 .. 4000 columns), every k, five value laws (dense
+    binary of random density, uniform ternary, rows copied from a few prototypes, 2 % non-zeros, all ones)
+    and batch sizes 1 .. 33; both activation types, host- and device-built index alternating."""
+    import torch
+
+    g = rng(20241106)
+    st = torch.cuda.current_stream().cuda_stream
+    for case in range(40):
+        rows = int(g.choice([1, 2, 5, 31, 33, 64, 65, 127, 500, 1000, 2047, 3000, 7000, 20000]))
+        cols = int(g.choice([1, 7, 64, 300, 1500, 4000]))
+        k = int(g.integers(1, 17))
+        kind = str(g.choice(["bin", "ter", "proto", "sparse", "ones"]))
+        if kind == "bin":
+            A = (g.random((rows, cols)) < g.uniform(0.05, 0.95)).astype(np.int8)
+        elif kind == "ter":
+            A = g.integers(-1, 2, size=(rows, cols)).astype(np.int8)
+        elif kind == "proto":
+            P = g.integers(-1, 2, size=(int(g.integers(1, 6)), cols)).astype(np.int8)
+            A = P[g.integers(0, len(P), size=rows)].copy()
+            flip = g.random(A.shape) < 0.02
+            A[flip] = g.integers(-1, 2, size=int(flip.sum()))
+        elif kind == "sparse":
+            A = ((g.random((rows, cols)) < 0.02) * g.choice([-1, 1], size=(rows, cols))).astype(np.int8)
+        else:
+            A = np.ones((rows, cols), np.int8)
+        batch = int(g.choice([1, 2, 5, 9, 33]))
+        on_device = case % 2 == 1
+        note(f"random case {case}: {kind} {rows}x{cols} k={k} batch={batch} index built on the {'device' if on_device else 'host'}")
+        v8 = g.integers(-128, 128, size=(batch, rows), dtype=np.int8)
+        vf = g.standard_normal((batch, rows)).astype(np.float32)
+        if on_device:
+            dA = torch.from_numpy(A).cuda()
+            h = R.rsr_preprocess_device(dA, rows, cols, k)
+        else:
+            h = R.rsr_preprocess(A, k)
+        try:
+            o8 = torch.full((batch, cols), -7, dtype=torch.int32, device="cuda")
+            of = torch.full((batch, cols), float("nan"), dtype=torch.float32, device="cuda")
+            R.rsr_matvec_i8(h, torch.from_numpy(v8).cuda(), o8, batch, st)
+            R.rsr_matvec(h, torch.from_numpy(vf).cuda(), of, batch, st)
+            torch.cuda.synchronize()
+            assert np.array_equal(o8.cpu().numpy().astype(np.int64), dense.matvec_i8(A, v8)), case
+            assert_f32_close(of.cpu().numpy(), dense.matvec_f32(A, vf), vf)
+        finally:
+            torch.cuda.synchronize()
+            R.rsr_destroy(h)
+
+
 # ---- out += scale * (v . A), and matrices with q bits per entry as weighted binary planes ---------------
 def test_scaled_accumulation_into_the_result():
     import torch
