@@ -376,6 +376,31 @@ def main():
         torch.cuda.synchronize()
         warm_us = w0.elapsed_time(w1) * 1e3 / wsteps
 
+    # ---- independent products on two streams (context, never `value`): the start of one launch overlaps the
+    #      end of its neighbour, which is what a serving loop with independent requests sees ---------------------
+    two_stream_us = None
+    if not args.plain and not dense_mode and ncopies % 2 == 0:
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        dout2 = torch.zeros_like(dout)
+        targets = ((s1.cuda_stream, po), (s2.cuda_stream, dout2.data_ptr()))
+        tsteps = max(40, min(args.steps, 2000)) // 2 * 2
+
+        def run2(n):
+            for i in range(n):   # handle i on stream i % 2: no handle is used on both streams at once
+                st_, out_ = targets[i % 2]
+                if fn(handles[i % ncopies], pv, out_, args.batch, st_) != 0:
+                    raise RuntimeError(R.rsr_last_error())
+
+        torch.cuda.synchronize()
+        run2(100)
+        torch.cuda.synchronize()
+        b1, b2, f1, f2 = (torch.cuda.Event(enable_timing=True) for _ in range(4))
+        b1.record(s1); b2.record(s2)
+        run2(tsteps)
+        f1.record(s1); f2.record(s2)
+        torch.cuda.synchronize()
+        two_stream_us = max(b1.elapsed_time(f1), b1.elapsed_time(f2), b2.elapsed_time(f1), b2.elapsed_time(f2)) * 1e3 / tsteps
+
     ms_per_step = wall * 1e3 / args.steps
     launch_us = dev_ms * 1e3 / args.steps
     elem = 4 if args.dtype == "f32" else 1
@@ -427,6 +452,7 @@ def main():
             "launch_us_median": per_group[len(per_group) // 2],
             "launch_us_min": per_group[0],
             "warm_launch_us": warm_us,
+            "two_stream_us_per_product": two_stream_us,
         },
     }
     if not args.no_cpu:
