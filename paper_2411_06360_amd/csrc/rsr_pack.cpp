@@ -40,6 +40,7 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // the one whose bank has been picked least at that position.
 constexpr int kBanks = 32;
 constexpr int kHalf = 32;
+constexpr int kImprovePasses = 4;
 
 void spread_over_banks(uint16_t (*ent)[kMaxPositions], const uint8_t (*flg)[kMaxPositions], int npos, uint16_t null_index) {
   for (int h = 0; h < kLanes / kHalf; ++h) {
@@ -69,6 +70,40 @@ void spread_over_banks(uint16_t (*ent)[kMaxPositions], const uint8_t (*flg)[kMax
         std::swap(ent[L][p], ent[L][best]);
         if (ent[L][p] != null_index) ++load[ent[L][p] % kBanks];
       }
+    }
+    // Then a few passes of local improvement: two rows of one run trade places when that lowers the sum of
+    // the squared bank loads of their two positions (a cheap stand-in for the depth of the fullest bank).
+    static thread_local uint8_t bank_load[kMaxPositions][kBanks];
+    for (int p = 0; p < npos; ++p) {
+      for (int b = 0; b < kBanks; ++b) bank_load[p][b] = 0;
+      for (int l = 0; l < kHalf; ++l)
+        if (ent[h * kHalf + l][p] != null_index) ++bank_load[p][ent[h * kHalf + l][p] % kBanks];
+    }
+    for (int pass = 0; pass < kImprovePasses; ++pass) {
+      bool changed = false;
+      for (int l = 0; l < kHalf; ++l) {
+        const int L = h * kHalf + l;
+        int p0 = 0;
+        while (p0 < npos) {
+          int p1 = p0 + 1;
+          while (p1 < npos && !flg[L][p1]) ++p1;  // the run [p0, p1)
+          for (int p = p0; p < p1; ++p)
+            for (int q = p + 1; q < p1; ++q) {
+              const uint16_t rp = ent[L][p], rq = ent[L][q];
+              if (rp == null_index || rq == null_index) continue;
+              const int bp = rp % kBanks, bq = rq % kBanks;
+              if (bp == bq) continue;
+              const int delta = ((int)bank_load[p][bq] - (int)bank_load[p][bp] + 1) + ((int)bank_load[q][bp] - (int)bank_load[q][bq] + 1);
+              if (delta < 0) {
+                --bank_load[p][bp]; ++bank_load[p][bq]; --bank_load[q][bq]; ++bank_load[q][bp];
+                std::swap(ent[L][p], ent[L][q]);
+                changed = true;
+              }
+            }
+          p0 = p1;
+        }
+      }
+      if (!changed) break;
     }
   }
 }
