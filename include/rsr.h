@@ -74,9 +74,10 @@ rsr_handle *rsr_preprocess(const int8_t *A, int64_t rows, int64_t cols, int k);
  * counting sort that yields the permutation (the bucket sort in the proof of Theorem 3.6), the full
  * segmentation (Section 3.3) and the packing all happen on the device; the host only turns per-window
  * entry counts into the schedule.  The handle is used exactly like one from rsr_preprocess and encodes
- * the same index (rsr_export_block returns identical tables).  One difference in speed, none in
- * results beyond float summation order: rsr_preprocess also orders the rows inside every group of
- * equal rows so that the gathers spread over the LDS banks, which this call does not do.
+ * the same index (rsr_export_block returns identical tables).  Both builders order the rows inside
+ * every group of equal rows so that the gathers of the product spread over the LDS banks; their
+ * searches differ, so the two packed streams may differ in that order (and float results in their
+ * summation order), not in the index or in the speed of the product.
  *
  *   A     DEVICE pointer, row-major rows x cols int8 in {-1,0,1}; read during the call only.
  *   rows, cols, k   as for rsr_preprocess.

@@ -12,8 +12,8 @@
 //   (host)               the unit descriptors and stream offsets from those counts: O(windows), no row data.
 //   4. emit_kernel       per unit: the entries dealt out to the 64 lanes, row indices in granule order, flags.
 //
-// The rows of a segment stay in ascending order here; the host packer (rsr_pack.cpp) additionally deals
-// them out over the LDS banks, which only changes the speed of the product, not the index it encodes.
+// Inside emit_kernel the rows of a segment are then dealt out over the LDS banks (as the host packer does in
+// rsr_pack.cpp, by the same exchange rule): that changes the speed of the product, not the index it encodes.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -161,6 +161,8 @@ __global__ void __launch_bounds__(256)
 emit_kernel(const UnitJob* __restrict__ jobs, Unit* __restrict__ units, const uint32_t* __restrict__ off,
             const uint16_t* __restrict__ sigma, int rows, int k, int kw, uint16_t* __restrict__ stream) {
   __shared__ uint32_t cnt[512], estart[513], f0[64], f1[64], wsum[4];
+  __shared__ uint16_t ent[64 * rsr::kMaxPositions];            // the unit's entries, [lane][position]
+  __shared__ uint32_t bank_load[2][rsr::kMaxPositions][32];    // rows per LDS bank, per half wavefront and position
   __shared__ int first_s, last_s;
   __shared__ uint32_t nrows_s, nheads_s;
   const int u = blockIdx.x, tid = threadIdx.x;
@@ -221,6 +223,62 @@ emit_kernel(const UnitJob* __restrict__ jobs, Unit* __restrict__ units, const ui
       flag = (i == estart[j]) && idx > 0;
       if (idx == 0) units[u].slot0 = (uint16_t)j;
     }
+    ent[l * rsr::kMaxPositions + p] = row;
+    if (flag) {
+      ++my_heads;
+      if (p < 32) atomicOr(&f0[l], 1u << (31 - p)); else atomicOr(&f1[l], 1u << (47 - p));
+    }
+  }
+  if (my_rows) atomicAdd(&nrows_s, my_rows);
+  if (my_heads) atomicAdd(&nheads_s, my_heads);
+  for (int i = tid; i < 2 * rsr::kMaxPositions * 32; i += 256) (&bank_load[0][0][0])[i] = 0;
+  __syncthreads();
+  // The order of the rows inside a segment is free.  As in the host packer, two rows of a lane's run that
+  // lies in one segment trade places while that lowers the squared loads of the LDS banks (row mod 32) at
+  // their two positions, counted per half wavefront: the gathers of the product then meet in fewer banks.
+  // One thread per lane; the loads are kept with atomics, a decision may see a neighbour's move late, which
+  // only costs quality.
+  if (tid < 64) {
+    const int L = tid, h = L >> 5;
+    for (int p = 0; p < npos; ++p) {
+      const uint16_t r = ent[L * rsr::kMaxPositions + p];
+      if (r != null_index) atomicAdd(&bank_load[h][p][r & 31], 1u);
+    }
+  }
+  __syncthreads();
+  for (int pass = 0; pass < 6; ++pass) {
+    if (tid < 64) {
+      const int L = tid, h = L >> 5;
+      const uint32_t g0 = f0[L], g1 = f1[L];
+      auto flagged = [&](int q) { return q < 32 ? (g0 >> (31 - q)) & 1u : (g1 >> (47 - q)) & 1u; };
+      uint16_t* e = ent + L * rsr::kMaxPositions;
+      int p0 = 0;
+      while (p0 < npos) {
+        int p1 = p0 + 1;
+        while (p1 < npos && !flagged(p1)) ++p1;
+        for (int pp = p0; pp < p1; ++pp)
+          for (int q = pp + 1; q < p1; ++q) {
+            const uint16_t rp = e[pp], rq = e[q];
+            if (rp == null_index || rq == null_index) continue;
+            const int bp = rp & 31, bq = rq & 31;
+            if (bp == bq) continue;
+            volatile uint32_t* lp = bank_load[h][pp];
+            volatile uint32_t* lq = bank_load[h][q];
+            const int delta = ((int)lp[bq] - (int)lp[bp] + 1) + ((int)lq[bp] - (int)lq[bq] + 1);
+            if (delta < 0) {
+              atomicSub(&bank_load[h][pp][bp], 1u); atomicAdd(&bank_load[h][pp][bq], 1u);
+              atomicSub(&bank_load[h][q][bq], 1u); atomicAdd(&bank_load[h][q][bp], 1u);
+              e[pp] = rq; e[q] = rp;
+            }
+          }
+        p0 = p1;
+      }
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < 64 * npos; idx += 256) {
+    const int l = idx / npos, p = idx - l * npos;
+    const uint16_t row = ent[l * rsr::kMaxPositions + p];
     int64_t at;
     if (p < full * 8) {
       at = ((int64_t)(p / 8) * 64 + l) * 8 + (p % 8);
@@ -230,14 +288,7 @@ emit_kernel(const UnitJob* __restrict__ jobs, Unit* __restrict__ units, const ui
       at = ((npos & 1) && p == npos - 1) ? rest + (int64_t)(q / 2) * 2 * 64 + l : rest + ((int64_t)(q / 2) * 64 + l) * 2 + (q & 1);
     }
     stream[sbase + at] = row;
-    if (flag) {
-      ++my_heads;
-      if (p < 32) atomicOr(&f0[l], 1u << (31 - p)); else atomicOr(&f1[l], 1u << (47 - p));
-    }
   }
-  if (my_rows) atomicAdd(&nrows_s, my_rows);
-  if (my_heads) atomicAdd(&nheads_s, my_heads);
-  __syncthreads();
   if (tid < 64) {
     const int64_t fb = sbase + (int64_t)npos * 64;
     stream[fb + 2 * tid] = (uint16_t)(f0[tid] & 0xffffu);
