@@ -44,7 +44,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published peak HBM3E bandwidth
 PROFILED_TRAFFIC = {
     ("binary_16k", 1, "f32", "cold"): {"table_bytes": 49610972, "traffic_bytes": 51.03e6,
                                        "source": "profiles/rsr_matvec_f32_binary16k_b1_cold.md"},
-    ("binary_16k", 8, "f32", "cold"): {"table_bytes": 49610972, "traffic_bytes": 60.71e6,
+    ("binary_16k", 8, "f32", "cold"): {"table_bytes": 49610972, "traffic_bytes": 60.05e6,
                                        "source": "profiles/rsr_matvec_f32_binary16k_b8_cold.md"},
 }
 PRECONDITION_LAUNCHES = 3000   # untimed, before the warm-up steps (see main)
