@@ -453,6 +453,8 @@ def main():
             "launch_us_min": per_group[0],
             "warm_launch_us": warm_us,
             "two_stream_us_per_product": two_stream_us,
+            "note": "priced against HBM as the metric asks; what the launch runs out of is the LDS of the compute units "
+                    "(a gather per row, a masked store per position)",
         },
     }
     if not args.no_cpu:
